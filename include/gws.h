@@ -1,0 +1,142 @@
+/*
+ * libgws -- Gaussian weight sampling (GaussWS) hot path for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
+ * every other pointer is host memory.  The library allocates no device memory,
+ * keeps no global state and is thread-safe.  All GPU work is enqueued
+ * asynchronously on the given stream (a hipStream_t passed as void*, NULL = the
+ * default stream); no call synchronises.  The return value is a gws_status and
+ * reports argument and launch errors only; on any error nothing has been
+ * launched for the failing call.
+ *
+ * Notation follows the paper: w is a BF16 weight matrix [rows x cols], split in
+ * square blocks of b_l = 32; b_t is the per-block bitwidth; R is the noise basis
+ * approximating round(N(0,1)/2); w_hat is the sampled weight.
+ *
+ * Noise identity between forward and backward (paper Sec. 3.5 "GPU memory",
+ * Sec. 3.6 "Managing seed"): R is a pure function of (seed, step, row, column),
+ * so a backward call with the seed and step of the forward call regenerates the
+ * same R and no noise tensor is ever stored.  The 16 random bits of element
+ * (i, j) are nibble (j & 7) of each of the four words of
+ *   Philox4x32-10(counter = (col0/8 + j>>3, row0 + i, step_lo, step_hi),
+ *                 key     = (seed_lo, seed_hi)).
+ */
+#ifndef GWS_H
+#define GWS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GWS_BLOCK 32 /* b_l, paper Sec. 3.2 */
+
+/* Target format fp_{e,m} of the cast that follows the addition (paper Sec. 3.3).
+ * The cast is block-scaled (MX style): with Ea = floor(log2 max|w|) of the block,
+ * values are rounded (nearest, ties to even, gradual underflow, saturating) to
+ * X * {codes of the format}, X = 2^(Ea + 1 - emax), which puts the format's top
+ * binade on the headroom binade that w_hat can reach (proof of Prop. 3).
+ * The result is stored in a BF16 container (2 bytes per parameter, Sec. 3.5). */
+typedef enum gws_format {
+  GWS_FMT_BF16 = 0,     /* no further rounding after the BF16 add             */
+  GWS_FMT_FP8_E4M3 = 1, /* OCP FP8 E4M3: emax 8, emin -6, 3 mantissa bits, max 448 */
+  GWS_FMT_FP6_E3M2 = 2  /* OCP MX FP6 E3M2: emax 4, emin -2, 2 mantissa bits, max 28 */
+} gws_format;
+
+typedef enum gws_status {
+  GWS_OK = 0,
+  GWS_ERR_NULL = 1,   /* a required pointer is NULL                              */
+  GWS_ERR_SHAPE = 2,  /* negative size, ld < cols, ld % 8 != 0, size >= 2^31,
+                         row0/col0 not a multiple of 32, n < 0                   */
+  GWS_ERR_ALIGN = 3,  /* BF16 pointer not 16-byte aligned, fp32 pointer not 4-byte */
+  GWS_ERR_FORMAT = 4, /* unknown gws_format                                      */
+  GWS_ERR_LAUNCH = 5, /* the HIP runtime refused a kernel launch                 */
+  GWS_ERR_ALIAS = 6   /* an output overlaps an input it must not overlap         */
+} gws_status;
+
+/* One weight tensor, row-major.  BF16 buffers are [rows x ld] with ld >= cols
+ * elements per row (ld a multiple of 8, base 16-byte aligned); columns >= cols
+ * of an output row are never written.  Per-block fp32 buffers are
+ * [ceil(rows/32) x ceil(cols/32)] row-major, dense.  rows or cols may be 0 (the
+ * tensor is then skipped) and need not be multiples of 32: an edge block holds
+ * only the elements that exist.                                                   */
+typedef struct gws_tensor {
+  const void* w;      /* device, BF16: weight (forward in)                        */
+  void* w_hat;        /* device, BF16: sampled weight (forward out); not w        */
+  const float* bt;    /* device, fp32 per block: bitwidth b_t (forward in)        */
+  float* scale;       /* device, fp32 per block: max|w| * 2^(1-b_t), unrounded
+                         fp32 (forward out, backward in)                          */
+  const void* g;      /* device, BF16: dL/dw_hat (backward in)                    */
+  void* dw;           /* device, BF16: dL/dw (backward out).  NULL or == g: the
+                         pass-through is an alias and nothing is copied           */
+  float* dbt;         /* device, fp32 per block: dL/db_t (backward out)           */
+  int64_t rows, cols; /* elements                                                 */
+  int64_t ld;         /* leading dimension of w, w_hat, g, dw (elements)          */
+  int64_t row0, col0; /* position of this tensor inside a larger, sharded tensor
+                         (multiples of 32; 0 for a whole tensor).  They only
+                         enter the noise counter, so shards reproduce the noise
+                         of the unsharded tensor                                  */
+  uint64_t seed;      /* per-tensor seed, see gws_derive_seed                     */
+} gws_tensor;
+
+/* Forward, paper Eq. 3 followed by the cast of Sec. 3.3, for n tensors in as few
+ * launches as possible:
+ *   a      = max_{b_l}|w|                                  (exact)
+ *   s32    = fp32(a) * 2^(1 - b_t)                         (fp32; 2^t is the
+ *            library's fixed degree-6 polynomial, exact for integer t)
+ *   s      = bf16_rne(s32)
+ *   w_hat  = cast_fmt( bf16_rne( w + R * s ) )
+ * where R * s is formed in sign-magnitude (R = -0 gives -0.0).  Writes w_hat and
+ * scale (= s32).  `t` is a host array of n descriptors; it is read before the
+ * call returns.  Uses fields w, w_hat, bt, scale, rows, cols, ld, row0, col0, seed. */
+int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* stream);
+
+/* Backward, paper Eq. 4, for n tensors:
+ *   dL/dw   = dL/dw_hat           (bit copy into dw unless dw is NULL or == g)
+ *   dL/db_t = -ln2 * s32 * sum_{b_l}( dL/dw_hat .* R )      (fp32, fixed order)
+ * with R regenerated from (seed, step) and s32 read from `scale` as the forward
+ * call left it.  Uses fields g, dw, dbt, scale, rows, cols, ld, row0, col0, seed. */
+int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream);
+
+/* Fused sampled-weight linear: Y = X * w_hat with w_hat produced as in
+ * gws_sample_fwd inside the GEMM's weight-operand path (the paper, Sec. 3.5
+ * "Separate kernels", keeps these apart; this is the fused alternative).
+ *   x : device BF16 [M x K], leading dimension ldx
+ *   w : one descriptor (host).  w->w is [K x N] (rows = K, cols = N) or, when
+ *       w_is_nk != 0, [N x K] (rows = N, cols = K; Y = X * w_hat^T).
+ *       w->w_hat and w->scale are written if non-NULL (both or neither).
+ *   y : device BF16 [M x N], leading dimension ldy; fp32 accumulation, one
+ *       round-to-nearest-even to BF16.
+ * K and N must be multiples of 32; ldx, ldy multiples of 8.                       */
+int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
+                   const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
+                   void* y, int64_t ldy, void* stream);
+
+/* Plain BF16 GEMM with the same tiling as gws_linear_fwd and no sampling:
+ * Y = X * W (or X * W^T when w_is_nk).  The reference point the fused kernel's
+ * overhead is measured against.  w is device BF16 with leading dimension ldw.     */
+int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx,
+                  const void* w, int64_t N, int64_t ldw, int w_is_nk,
+                  void* y, int64_t ldy, void* stream);
+
+/* The packed noise alone (paper Sec. 3.4: sign-magnitude, 4 bits per element,
+ * 8 elements per 32-bit word): out is device u32 [rows x ceil(cols/8)], element
+ * k of a group in bits 4k..4k+3, code = sign<<3 | |R|.  The training path never
+ * materialises this tensor; the entry point exists to inspect R.                  */
+int gws_noise_packed(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0,
+                     uint64_t seed, uint64_t step, void* stream);
+
+/* Per-tensor seed from a user seed (paper Sec. 3.6: layers must draw independent
+ * R).  Pure host function: low 64 bits of Philox4x32-10(counter = (id_lo, id_hi,
+ * 0x47575331, 0), key = user seed).  The training loop passes step = index of the
+ * gradient update, which replaces the paper's per-layer PRNG state.               */
+uint64_t gws_derive_seed(uint64_t user_seed, uint64_t tensor_id);
+
+const char* gws_status_string(int status);
+int gws_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GWS_H */

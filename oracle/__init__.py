@@ -1,0 +1,210 @@
+"""GaussWS CPU oracle: TEST INFRASTRUCTURE ONLY.
+
+ctypes front end of ``gws_oracle.c`` (plain C, fp64 reductions, integer-emulated
+BF16 arithmetic).  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package; the product package
+never does, and this package never imports the product.
+
+BF16 tensors are exchanged as ``numpy.uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gws_oracle.c")
+_LIB = os.path.join(_HERE, "libgws_oracle.so")
+
+FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (host only, no HIP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        vp, i64, u64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+        L.gwso_set_threads.argtypes = [ci]
+        L.gwso_set_threads.restype = ci
+        L.gwso_philox4x32.argtypes = [u32p, u32p, ci, u32p]
+        L.gwso_philox4x32.restype = None
+        L.gwso_derive_seed.argtypes = [u64, u64]
+        L.gwso_derive_seed.restype = u64
+        L.gwso_nibbles_to_code.argtypes = [ctypes.c_uint] * 4
+        L.gwso_nibbles_to_code.restype = ci
+        L.gwso_code_to_r.argtypes = [ci]
+        L.gwso_code_to_r.restype = ci
+        L.gwso_noise.argtypes = [i64, i64, i64, i64, u64, u64, vp, vp]
+        L.gwso_noise.restype = None
+        L.gwso_bf16_rne.argtypes = [ctypes.c_float]
+        L.gwso_bf16_rne.restype = ctypes.c_uint16
+        L.gwso_bf16_add.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
+        L.gwso_bf16_add.restype = ctypes.c_uint16
+        L.gwso_exp2.argtypes = [ctypes.c_float]
+        L.gwso_exp2.restype = ctypes.c_float
+        L.gwso_cast.argtypes = [ctypes.c_uint16, ci, ci]
+        L.gwso_cast.restype = ctypes.c_uint16
+        L.gwso_bf16_add_n.argtypes = [vp, vp, vp, i64]
+        L.gwso_bf16_add_n.restype = None
+        L.gwso_cast_n.argtypes = [vp, ci, ci, vp, i64]
+        L.gwso_cast_n.restype = None
+        L.gwso_exp2_n.argtypes = [vp, vp, i64]
+        L.gwso_exp2_n.restype = None
+        L.gwso_sample_fwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, u64, u64, vp, vp]
+        L.gwso_sample_fwd.restype = ci
+        L.gwso_sample_bwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, u64, u64, vp, vp, vp]
+        L.gwso_sample_bwd.restype = ci
+        L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
+        L.gwso_linear_fwd.restype = ci
+        _lib = L
+    return _lib
+
+
+def set_threads(n: int) -> int:
+    return lib().gwso_set_threads(int(n))
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def philox4x32(ctr, key, rounds: int = 10):
+    c = (ctypes.c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])
+    o = (ctypes.c_uint32 * 4)()
+    lib().gwso_philox4x32(c, k, rounds, o)
+    return [int(v) for v in o]
+
+
+def derive_seed(user_seed: int, tensor_id: int) -> int:
+    return int(lib().gwso_derive_seed(user_seed & (2**64 - 1), tensor_id & (2**64 - 1)))
+
+
+def nibbles_to_code(n0, n1, n2, n3) -> int:
+    return int(lib().gwso_nibbles_to_code(n0, n1, n2, n3))
+
+
+def code_to_r(code: int) -> int:
+    return int(lib().gwso_code_to_r(code))
+
+
+def noise(rows: int, cols: int, seed: int, step: int, row0: int = 0, col0: int = 0):
+    """Returns (R int8 [rows, cols], packed uint32 [rows, ceil(cols/8)])."""
+    assert col0 % 8 == 0
+    r = np.empty((rows, cols), dtype=np.int8)
+    packed = np.empty((rows, (cols + 7) // 8), dtype=np.uint32)
+    lib().gwso_noise(rows, cols, row0, col0, seed, step, _ptr(r), _ptr(packed))
+    return r, packed
+
+
+def bf16_rne(f: float) -> int:
+    return int(lib().gwso_bf16_rne(f))
+
+
+def bf16_add(a: int, b: int) -> int:
+    return int(lib().gwso_bf16_add(a, b))
+
+
+def exp2(t: float) -> float:
+    return float(lib().gwso_exp2(t))
+
+
+def cast(v16: int, Ea: int, fmt: int) -> int:
+    return int(lib().gwso_cast(v16, Ea, fmt))
+
+
+def bf16_add_n(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    assert a.shape == b.shape
+    out = np.empty_like(a)
+    lib().gwso_bf16_add_n(_ptr(a), _ptr(b), _ptr(out), a.size)
+    return out
+
+
+def cast_n(v: np.ndarray, Ea: int, fmt: int) -> np.ndarray:
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    out = np.empty_like(v)
+    lib().gwso_cast_n(_ptr(v), Ea, fmt, _ptr(out), v.size)
+    return out
+
+
+def exp2_n(t: np.ndarray) -> np.ndarray:
+    t = np.ascontiguousarray(t, dtype=np.float32)
+    out = np.empty_like(t)
+    lib().gwso_exp2_n(_ptr(t), _ptr(out), t.size)
+    return out
+
+
+def n_blocks(rows: int, cols: int):
+    return (rows + 31) // 32, (cols + 31) // 32
+
+
+def sample_fwd(w: np.ndarray, bt: np.ndarray, fmt: int, seed: int, step: int, cols: int | None = None,
+               row0: int = 0, col0: int = 0):
+    """w: uint16 [rows, ld] (BF16 bits), bt: float32 [nbr, nbc].
+    `cols` defaults to w.shape[1] (= ld).  Returns (w_hat uint16 like w, scale float32)."""
+    assert w.dtype == np.uint16 and w.ndim == 2 and w.flags.c_contiguous
+    rows, ld = w.shape
+    cols = ld if cols is None else cols
+    nbr, nbc = n_blocks(rows, cols)
+    bt = np.ascontiguousarray(bt, dtype=np.float32).reshape(nbr, nbc)
+    w_hat = w.copy()  # padding columns (>= cols) keep the input bytes
+    scale = np.empty((nbr, nbc), dtype=np.float32)
+    rc = lib().gwso_sample_fwd(_ptr(w), rows, cols, ld, row0, col0, _ptr(bt), fmt, seed, step, _ptr(w_hat), _ptr(scale))
+    if rc:
+        raise RuntimeError(f"gwso_sample_fwd status {rc}")
+    return w_hat, scale
+
+
+def sample_bwd(g: np.ndarray, scale: np.ndarray, seed: int, step: int, cols: int | None = None,
+               row0: int = 0, col0: int = 0):
+    """g: uint16 [rows, ld].  Returns (dw uint16, dbt float64 [nbr,nbc], abs_sum float64)."""
+    assert g.dtype == np.uint16 and g.ndim == 2 and g.flags.c_contiguous
+    rows, ld = g.shape
+    cols = ld if cols is None else cols
+    nbr, nbc = n_blocks(rows, cols)
+    scale = np.ascontiguousarray(scale, dtype=np.float32).reshape(nbr, nbc)
+    dw = np.zeros_like(g)
+    dbt = np.empty((nbr, nbc), dtype=np.float64)
+    asum = np.empty((nbr, nbc), dtype=np.float64)
+    rc = lib().gwso_sample_bwd(_ptr(g), rows, cols, ld, row0, col0, _ptr(scale), seed, step, _ptr(dw), _ptr(dbt), _ptr(asum))
+    if rc:
+        raise RuntimeError(f"gwso_sample_bwd status {rc}")
+    return dw, dbt, asum
+
+
+def linear_fwd(x: np.ndarray, q: np.ndarray, w_is_nk: bool = False, rows_sel=None):
+    """x: uint16 [M, K]; q: uint16 [K, N] (or [N, K] if w_is_nk).
+    Returns (y64 [R, N], yabs [R, N], y16 uint16 [R, N]) for the selected rows."""
+    assert x.dtype == np.uint16 and q.dtype == np.uint16
+    M, K = x.shape
+    N = q.shape[0] if w_is_nk else q.shape[1]
+    assert (q.shape[1] if w_is_nk else q.shape[0]) == K
+    sel = None if rows_sel is None else np.ascontiguousarray(rows_sel, dtype=np.int64)
+    R = M if sel is None else len(sel)
+    y64 = np.empty((R, N), dtype=np.float64)
+    yabs = np.empty((R, N), dtype=np.float64)
+    y16 = np.empty((R, N), dtype=np.uint16)
+    rc = lib().gwso_linear_fwd(_ptr(x), M, K, x.shape[1], _ptr(q), N, q.shape[1], int(w_is_nk),
+                               _ptr(sel), R, _ptr(y64), _ptr(yabs), _ptr(y16))
+    if rc:
+        raise RuntimeError(f"gwso_linear_fwd status {rc}")
+    return y64, yabs, y16

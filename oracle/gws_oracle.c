@@ -1,0 +1,462 @@
+/*
+ * GaussWS CPU oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, obviously-correct implementation of the Gaussian weight
+ * sampling forward/backward (paper Sec. 3.2 Eq. 3 and Eq. 4, noise basis of
+ * Sec. 3.4 Eq. 10, FP cast fp_{e,m} of Sec. 3.3) used to check the HIP
+ * kernels.  Only tests, the smoke check and the benchmark's cpu_baseline leg
+ * may call it; the product path never does.  It shares no code, header or
+ * table with the HIP path: every constant below is typed in here on its own.
+ *
+ * Every function follows the steps in the paper's order, one element at a
+ * time, with no blocking or fusion beyond the 32x32 block the method itself
+ * defines.  Floating point that decides a stored bit pattern (block scale,
+ * BF16 add, casts) is emulated on integers or evaluated with explicitly
+ * sequenced fp32 operations so the result is a single defined bit pattern;
+ * reductions (Eq. 4's block sum, the GEMM) are done in fp64.
+ *
+ * Parity pins (tests/test_oracle_*.py): Philox known-answer vectors, the
+ * exhaustive 2^16 enumeration of the bit->R map against Eq. 10's closed form,
+ * torch CPU bfloat16 adds, torch CPU float8_e4m3fn casts, brute-force nearest
+ * search over the enumerated FP6-E3M2 / FP8-E4M3 code sets, hand-worked
+ * blocks, Table C.1, finite differences of Eq. 3 for Eq. 4.
+ * Nothing here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define GWSO_BL 32 /* b_l: square block edge, Sec. 3.2 */
+
+enum { GWSO_FMT_BF16 = 0, GWSO_FMT_FP8_E4M3 = 1, GWSO_FMT_FP6_E3M2 = 2 };
+
+/* ------------------------------------------------------------------ */
+/* Threads (only used by the benchmark's cpu_baseline leg)             */
+/* ------------------------------------------------------------------ */
+int gwso_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+  return omp_get_max_threads();
+#else
+  (void)n;
+  return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ */
+/* Philox4x32 (Salmon et al., SC'11), the counter-based bit source the  */
+/* paper names in Sec. 3.4.  `rounds` = 10 is the standard generator.   */
+/* ------------------------------------------------------------------ */
+void gwso_philox4x32(const uint32_t ctr[4], const uint32_t key[2], int rounds,
+                     uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int r = 0; r < rounds; ++r) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Per-tensor seed: replaces the paper's stateful per-layer PRNG (Sec. 3.6,
+ * "Managing seed") by a pure function of (user seed, tensor id).            */
+uint64_t gwso_derive_seed(uint64_t user_seed, uint64_t tensor_id) {
+  uint32_t ctr[4] = {(uint32_t)tensor_id, (uint32_t)(tensor_id >> 32), 0x47575331u, 0u};
+  uint32_t key[2] = {(uint32_t)user_seed, (uint32_t)(user_seed >> 32)};
+  uint32_t o[4];
+  gwso_philox4x32(ctr, key, 10, o);
+  return (uint64_t)o[0] | ((uint64_t)o[1] << 32);
+}
+
+/* ------------------------------------------------------------------ */
+/* Random bits -> R (Sec. 3.4, Eq. 9 and Eq. 10).                      */
+/* An element owns 16 independent bits, given here as four nibbles      */
+/* n0..n3.  Built only from AND/OR of independent bits:                 */
+/*   |R|=2  <=> (b or b) and (8 bits all set)          : 3/4 * 2^-8     */
+/*   |R|=1  <=> (b or b) and (b or b) and b, not |R|=2 : (3/4)^2 * 2^-1 */
+/*   sign   <=> one bit                                                 */
+/* Returns the 4-bit sign-magnitude code (sign<<3 | magnitude).         */
+/* ------------------------------------------------------------------ */
+int gwso_nibbles_to_code(unsigned n0, unsigned n1, unsigned n2, unsigned n3) {
+  int all8 = (n0 == 0xFu) && (n1 == 0xFu);
+  int A = (n2 & 0x3u) != 0;
+  int C = (n2 & 0xCu) != 0;
+  int D = (n3 & 0x3u) != 0;
+  int E = (n3 >> 2) & 1;
+  int S = (n3 >> 3) & 1;
+  int mag2 = all8 && A;
+  int mag1 = C && D && E && !mag2;
+  return (S << 3) | (mag2 << 1) | mag1;
+}
+
+/* code -> integer R in {-2,-1,0,1,2} */
+int gwso_code_to_r(int code) {
+  int mag = code & 3;
+  return (code & 8) ? -mag : mag;
+}
+
+/* The four Philox words of the group of 8 row-contiguous elements that
+ * holds element (i, j): counter = (column group j>>3, row i, step lo, step hi),
+ * key = per-tensor seed.  Forward and backward call this with the same
+ * (seed, step), which is what makes R identical in both (Sec. 3.5, 3.6).     */
+static void group_words(int64_t i, int64_t cg, uint64_t seed, uint64_t step,
+                        uint32_t x[4]) {
+  uint32_t ctr[4] = {(uint32_t)cg, (uint32_t)i, (uint32_t)step, (uint32_t)(step >> 32)};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  gwso_philox4x32(ctr, key, 10, x);
+}
+
+/* Element k (= j & 7) of a group takes nibble k of each word. */
+static int element_code(const uint32_t x[4], int k) {
+  return gwso_nibbles_to_code((x[0] >> (4 * k)) & 0xFu, (x[1] >> (4 * k)) & 0xFu,
+                              (x[2] >> (4 * k)) & 0xFu, (x[3] >> (4 * k)) & 0xFu);
+}
+
+/* Noise of a whole [rows x cols] tensor.
+ *   r      : int8 [rows x cols] (may be NULL), R values
+ *   packed : u32  [rows x ceil(cols/8)] (may be NULL), 8 codes per word,
+ *            element k of the group in bits 4k..4k+3 (Sec. 3.4, packed format)
+ * (row0, col0): where this tensor sits inside a larger one (col0 a multiple of
+ * 8); they only shift the counter, so a shard sees the full tensor's noise.     */
+void gwso_noise(int64_t rows, int64_t cols, int64_t row0, int64_t col0, uint64_t seed,
+                uint64_t step, int8_t* r, uint32_t* packed) {
+  int64_t ngrp = (cols + 7) / 8;
+  for (int64_t i = 0; i < rows; ++i) {
+    for (int64_t cg = 0; cg < ngrp; ++cg) {
+      uint32_t x[4];
+      group_words(row0 + i, col0 / 8 + cg, seed, step, x);
+      uint32_t word = 0;
+      for (int k = 0; k < 8; ++k) {
+        int code = element_code(x, k);
+        word |= (uint32_t)code << (4 * k);
+        int64_t j = cg * 8 + k;
+        if (r && j < cols) r[i * cols + j] = (int8_t)gwso_code_to_r(code);
+      }
+      if (packed) packed[i * ngrp + cg] = word;
+    }
+  }
+}
+
+/* ------------------------------------------------------------------ */
+/* BF16 helpers: values travel as uint16 bit patterns.                  */
+/* ------------------------------------------------------------------ */
+static float bf16_to_f32(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+static uint32_t f32_bits(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  return u;
+}
+
+/* fp32 -> BF16, round to nearest, ties to even (finite inputs). */
+uint16_t gwso_bf16_rne(float f) {
+  uint32_t u = f32_bits(f);
+  uint32_t lsb = (u >> 16) & 1u;
+  u += 0x7FFFu + lsb;
+  return (uint16_t)(u >> 16);
+}
+
+/* Exact BF16 + BF16 -> BF16 with ONE round-to-nearest-even, on integers.
+ * Operands are decoded to sign / exponent / 8-bit significand; the smaller
+ * one is aligned with a sticky bit; the exact sum is normalised and rounded
+ * once.  Finite inputs; overflow gives infinity.  Sign of an exact zero sum
+ * follows IEEE 754 (x + (-x) = +0; (-0) + (-0) = -0).                        */
+uint16_t gwso_bf16_add(uint16_t a, uint16_t b) {
+  int sa = a >> 15, sb = b >> 15;
+  int ea = (a >> 7) & 0xFF, eb = (b >> 7) & 0xFF;
+  uint64_t ma = a & 0x7Fu, mb = b & 0x7Fu;
+  if (ea) ma |= 0x80u; else ea = 1; /* subnormal: exponent of the lowest binade */
+  if (eb) mb |= 0x80u; else eb = 1;
+  /* order so that |a| >= |b| */
+  if (eb > ea || (eb == ea && mb > ma)) {
+    int t = sa; sa = sb; sb = t;
+    t = ea; ea = eb; eb = t;
+    uint64_t m = ma; ma = mb; mb = m;
+  }
+  if (ma == 0) { /* both zero */
+    return (uint16_t)((sa && sb) ? 0x8000u : 0x0000u);
+  }
+  /* fixed point with 40 fraction bits below the BF16 lsb of a */
+  const int G = 40;
+  uint64_t A = ma << G, B;
+  int sh = ea - eb;
+  int sticky = 0;
+  if (sh >= G + 8) { B = 0; sticky = (mb != 0); }
+  else {
+    B = mb << G;
+    if (sh > 0) {
+      sticky = (B & ((1ull << sh) - 1)) != 0; /* always 0 for sh <= G */
+      B >>= sh;
+    }
+  }
+  uint64_t S;
+  if (sa == sb) S = A + B;
+  else {
+    S = A - B;
+    if (sticky) { S -= 1; } /* borrow: true value lies strictly between S-1 and S */
+  }
+  if (S == 0 && !sticky) return 0x0000u; /* exact cancellation -> +0 (RNE mode) */
+  /* S (plus sticky) * 2^(ea - 127 - 7 - G) is the exact magnitude */
+  int e = ea; /* exponent field if the leading one sits at bit G+7 */
+  while (S >= (1ull << (G + 8))) { sticky |= (int)(S & 1); S >>= 1; e += 1; }
+  while (S < (1ull << (G + 7)) && e > 1) { S <<= 1; e -= 1; }
+  /* round to 8 significant bits (or fewer when subnormal: e == 1, no hidden bit) */
+  uint64_t keep = S >> G;
+  uint64_t rem = S & ((1ull << G) - 1);
+  uint64_t half = 1ull << (G - 1);
+  int up = (rem > half) || (rem == half && (sticky || (keep & 1)));
+  keep += (uint64_t)up;
+  if (keep >= 0x100u) { keep >>= 1; e += 1; }       /* carried into the next binade */
+  uint32_t field;
+  if (keep < 0x80u) field = (uint32_t)keep;          /* subnormal or zero */
+  else field = ((uint32_t)e << 7) | (uint32_t)(keep & 0x7Fu);
+  if (keep >= 0x80u && e >= 0xFF) field = 0x7F80u;   /* overflow -> inf */
+  return (uint16_t)(((uint32_t)sa << 15) | field);
+}
+
+/* ------------------------------------------------------------------ */
+/* 2^t for the block scale 2^(1 - b_t) of Eq. 3, as ONE defined fp32    */
+/* function (b_t is a real-valued trained parameter, Sec. 3.6):         */
+/*   n = rint(t), f = t - n in [-1/2, 1/2] (exact),                     */
+/*   p = degree-6 Horner polynomial in f with fused multiply-adds,      */
+/*   result = p * 2^n.                                                  */
+/* Exact for integer t; below 1 ulp from the true 2^t elsewhere.        */
+/* ------------------------------------------------------------------ */
+float gwso_exp2(float t) {
+  static const uint32_t cbits[7] = {0x3F800000u, 0x3F317218u, 0x3E75FDF0u, 0x3D6357B6u,
+                                    0x3C1D950Eu, 0x3AAF844Bu, 0x39222002u};
+  float c[7];
+  memcpy(c, cbits, sizeof c);
+  float n = rintf(t);            /* ties to even (default rounding mode) */
+  float f = t - n;
+  float p = c[6];
+  for (int i = 5; i >= 0; --i) p = fmaf(p, f, c[i]);
+  return ldexpf(p, (int)n);
+}
+
+/* ------------------------------------------------------------------ */
+/* fp_{e,m} cast of Sec. 3.3, read as a block-scaled (MX-style) cast:   */
+/* the format's top binade is placed one above the binade of max|w|,    */
+/* the headroom binade that w_hat can reach (proof of Prop. 3).         */
+/*   X = 2^(Ea + 1 - emax),  q = X * sat( rne_{e,m}( v / X ) )          */
+/* with gradual underflow, ties to even, sign of zero kept, saturation   */
+/* to +-max*X.  v and q are BF16 bit patterns; q is exactly BF16-        */
+/* representable.  Ea = floor(log2 max|w|) of the block.                 */
+/* ------------------------------------------------------------------ */
+static void fmt_params(int fmt, int* emax, int* emin, int* m, double* maxv) {
+  if (fmt == GWSO_FMT_FP8_E4M3) { *emax = 8; *emin = -6; *m = 3; *maxv = 448.0; }
+  else { *emax = 4; *emin = -2; *m = 2; *maxv = 28.0; } /* FP6_E3M2 */
+}
+
+uint16_t gwso_cast(uint16_t v16, int Ea, int fmt) {
+  if (fmt == GWSO_FMT_BF16) return v16;
+  int emax, emin, m;
+  double maxv;
+  fmt_params(fmt, &emax, &emin, &m, &maxv);
+  int xe = Ea + 1 - emax;
+  double v = (double)bf16_to_f32(v16);
+  double y = ldexp(v, -xe);              /* exact: power-of-two scaling in fp64 */
+  double ay = fabs(y);
+  double q = 0.0;
+  if (ay != 0.0) {
+    int e = ilogb(ay);
+    if (e < emin) e = emin;              /* subnormal range of the target */
+    double quantum = ldexp(1.0, e - m);
+    q = quantum * nearbyint(ay / quantum); /* RNE; both steps exact */
+    if (q > maxv) q = maxv;              /* saturate */
+  }
+  double out = ldexp(q, xe);
+  float of = (float)out;                 /* exact */
+  uint16_t r = (uint16_t)(f32_bits(of) >> 16);
+  return (uint16_t)((v16 & 0x8000u) | (r & 0x7FFFu));
+}
+
+/* Array forms of the two scalar routines above, so that a test can sweep all
+ * 65 536 BF16 patterns without a Python-level loop. */
+void gwso_bf16_add_n(const uint16_t* a, const uint16_t* b, uint16_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = gwso_bf16_add(a[i], b[i]);
+}
+
+void gwso_cast_n(const uint16_t* v, int Ea, int fmt, uint16_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = gwso_cast(v[i], Ea, fmt);
+}
+
+void gwso_exp2_n(const float* t, float* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = gwso_exp2(t[i]);
+}
+
+/* floor(log2 a) for a positive finite BF16 value (subnormals included). */
+static int floor_log2_bf16(uint16_t a16) {
+  return ilogb((double)bf16_to_f32(a16));
+}
+
+/* ------------------------------------------------------------------ */
+/* Forward, Eq. 3 + cast, one tensor.                                   */
+/*   w, w_hat : BF16 [rows x cols], leading dimension ld (elements)     */
+/*   bt       : fp32 [ceil(rows/32) x ceil(cols/32)]                    */
+/*   scale    : out fp32 per block, s32 = max|w| * 2^(1-b_t) (unrounded */
+/*              fp32; Eq. 4 reuses it)                                   */
+/*   row0,col0: position inside a larger tensor (multiples of 32)       */
+/* ------------------------------------------------------------------ */
+int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
+                    int64_t row0, int64_t col0, const float* bt, int fmt,
+                    uint64_t seed, uint64_t step, uint16_t* w_hat, float* scale) {
+  if (!w || !bt || !w_hat || !scale) return 1;
+  if (fmt < 0 || fmt > 2) return 4;
+  int64_t nbr = (rows + GWSO_BL - 1) / GWSO_BL, nbc = (cols + GWSO_BL - 1) / GWSO_BL;
+#pragma omp parallel for schedule(static)
+  for (int64_t bi = 0; bi < nbr; ++bi) {
+    for (int64_t bj = 0; bj < nbc; ++bj) {
+      int64_t i0 = bi * GWSO_BL, j0 = bj * GWSO_BL;
+      int64_t i1 = i0 + GWSO_BL < rows ? i0 + GWSO_BL : rows;
+      int64_t j1 = j0 + GWSO_BL < cols ? j0 + GWSO_BL : cols;
+      /* max_{b_l}(|w|): exact, on the magnitude bits */
+      uint16_t a16 = 0;
+      for (int64_t i = i0; i < i1; ++i)
+        for (int64_t j = j0; j < j1; ++j) {
+          uint16_t mag = w[i * ld + j] & 0x7FFFu;
+          if (mag > a16) a16 = mag;
+        }
+      /* scale = max|w| * 2^(1-b_t): fp32, then one rounding to BF16 */
+      float t = 1.0f - bt[bi * nbc + bj];
+      float p = gwso_exp2(t);
+      float s32 = bf16_to_f32(a16) * p;
+      uint16_t s16 = gwso_bf16_rne(s32);
+      scale[bi * nbc + bj] = s32;
+      int Ea = a16 ? floor_log2_bf16(a16) : 0;
+      /* 2*s as a BF16 pattern (exact: exponent + 1), for |R| = 2 */
+      uint16_t s2_16 = gwso_bf16_rne(2.0f * bf16_to_f32(s16));
+      for (int64_t i = i0; i < i1; ++i) {
+        for (int64_t j = j0; j < j1; ++j) {
+          uint32_t x[4];
+          /* recomputed per element: plain, not fast */
+          group_words(row0 + i, (col0 + j) >> 3, seed, step, x);
+          int code = element_code(x, (int)(j & 7));
+          int mag = code & 3;
+          /* PQN = R * s in sign-magnitude form: the sign bit is placed as is,
+           * so R = "-0" gives -0.0 (Sec. 3.4: sign-mantissa reconstruction) */
+          uint16_t pqn = (uint16_t)((mag == 0 ? 0u : (mag == 1 ? s16 : s2_16)) |
+                                    ((code & 8) ? 0x8000u : 0u));
+          uint16_t sum = gwso_bf16_add(w[i * ld + j], pqn);
+          w_hat[i * ld + j] = (a16 == 0) ? sum : gwso_cast(sum, Ea, fmt);
+        }
+      }
+    }
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Backward, Eq. 4, one tensor.                                         */
+/*   g   : dL/dw_hat, BF16                                              */
+/*   dw  : out, = g bit for bit (may be NULL)                           */
+/*   dbt : out fp64 per block, -ln2 * s32 * sum(g .* R)                 */
+/*   abs_sum : out fp64 per block (may be NULL), ln2 * s32 * sum|g .* R|,*/
+/*             the scale of rounding error a fp32 reduction may show     */
+/* ------------------------------------------------------------------ */
+int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
+                    int64_t row0, int64_t col0, const float* scale, uint64_t seed,
+                    uint64_t step, uint16_t* dw, double* dbt, double* abs_sum) {
+  if (!g || !scale || !dbt) return 1;
+  int64_t nbr = (rows + GWSO_BL - 1) / GWSO_BL, nbc = (cols + GWSO_BL - 1) / GWSO_BL;
+  const double ln2 = 0.69314718055994530942;
+#pragma omp parallel for schedule(static)
+  for (int64_t bi = 0; bi < nbr; ++bi) {
+    for (int64_t bj = 0; bj < nbc; ++bj) {
+      int64_t i0 = bi * GWSO_BL, j0 = bj * GWSO_BL;
+      int64_t i1 = i0 + GWSO_BL < rows ? i0 + GWSO_BL : rows;
+      int64_t j1 = j0 + GWSO_BL < cols ? j0 + GWSO_BL : cols;
+      double acc = 0.0, aacc = 0.0;
+      for (int64_t i = i0; i < i1; ++i)
+        for (int64_t j = j0; j < j1; ++j) {
+          uint32_t x[4];
+          group_words(row0 + i, (col0 + j) >> 3, seed, step, x);
+          int r = gwso_code_to_r(element_code(x, (int)(j & 7)));
+          double term = (double)bf16_to_f32(g[i * ld + j]) * (double)r;
+          acc += term;
+          aacc += fabs(term);
+          if (dw) dw[i * ld + j] = g[i * ld + j];
+        }
+      double s = (double)scale[bi * nbc + bj];
+      dbt[bi * nbc + bj] = -ln2 * s * acc;
+      if (abs_sum) abs_sum[bi * nbc + bj] = ln2 * s * aacc;
+    }
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Linear forward with an already-sampled weight (Sec. 3.5: the matmul  */
+/* consumes w_hat; BF16 inputs, wide accumulation, Sec. 4).             */
+/*   x : BF16 [M x K] (ldx);  q : BF16 w_hat, [K x N] (ldq) or, when    */
+/*   w_is_nk, [N x K];  rows_sel : optional list of nsel row indices of  */
+/*   X to compute (NULL = all M rows).                                   */
+/*   y64 : out fp64 [nsel x N] exact-ish sums; yabs : out fp64, sum of   */
+/*   |x*q| per output (error scale); y16 : out BF16 of y64 (may be NULL) */
+/* ------------------------------------------------------------------ */
+static uint16_t bf16_from_double(double d) {
+  /* fp64 -> BF16 with one RNE: round on the fp64 bit pattern */
+  uint64_t u;
+  memcpy(&u, &d, 8);
+  uint64_t sign = u >> 63;
+  int e = (int)((u >> 52) & 0x7FF);
+  uint64_t man = u & 0xFFFFFFFFFFFFFull;
+  if (e == 0 && man == 0) return (uint16_t)(sign << 15);
+  int E = e - 1023;                       /* fp64 normal assumed (sums of BF16 products) */
+  uint64_t sig = man | (1ull << 52);      /* 53-bit significand */
+  int drop = 45;                          /* keep 8 bits */
+  if (E < -126) drop += (-126 - E);       /* BF16 subnormal */
+  if (drop > 60) return (uint16_t)(sign << 15);
+  uint64_t keep = sig >> drop, rem = sig & ((1ull << drop) - 1), half = 1ull << (drop - 1);
+  if (rem > half || (rem == half && (keep & 1))) keep += 1;
+  int ef = (E < -126) ? 0 : E + 127;
+  uint32_t field;
+  if (E < -126) field = (uint32_t)keep;   /* may carry into the lowest normal: still right */
+  else {
+    if (keep >= 0x100u) { keep >>= 1; ef += 1; }
+    field = ((uint32_t)ef << 7) | (uint32_t)(keep & 0x7F);
+    if (ef >= 0xFF) field = 0x7F80u;
+  }
+  return (uint16_t)((sign << 15) | field);
+}
+
+int gwso_linear_fwd(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
+                    const uint16_t* q, int64_t N, int64_t ldq, int w_is_nk,
+                    const int64_t* rows_sel, int64_t nsel,
+                    double* y64, double* yabs, uint16_t* y16) {
+  if (!x || !q || !y64) return 1;
+  int64_t R = rows_sel ? nsel : M;
+#pragma omp parallel for schedule(static)
+  for (int64_t rr = 0; rr < R; ++rr) {
+    int64_t mrow = rows_sel ? rows_sel[rr] : rr;
+    for (int64_t n = 0; n < N; ++n) {
+      double acc = 0.0, aacc = 0.0;
+      for (int64_t k = 0; k < K; ++k) {
+        double xv = (double)bf16_to_f32(x[mrow * ldx + k]);
+        double qv = (double)bf16_to_f32(w_is_nk ? q[n * ldq + k] : q[k * ldq + n]);
+        acc += xv * qv;
+        aacc += fabs(xv * qv);
+      }
+      y64[rr * N + n] = acc;
+      if (yabs) yabs[rr * N + n] = aacc;
+      if (y16) y16[rr * N + n] = bf16_from_double(acc);
+    }
+  }
+  return 0;
+}

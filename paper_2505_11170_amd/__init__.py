@@ -1,0 +1,11 @@
+"""GaussWS (Gaussian weight sampling) hot path for MI355X / gfx950.
+
+Thin ctypes binding over ``libgws.so`` (hand-written HIP kernels behind a C ABI).
+Importing the package does not load the library; calling any operation does, and
+raises if the library has not been built.  There is no CPU fallback.
+"""
+from . import synth  # noqa: F401
+from .binding import (  # noqa: F401
+    FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2, GwsError, TensorDesc, derive_seed, gws_derive_seed,
+    gws_linear_fwd, gws_noise_packed, gws_sample_bwd, gws_sample_fwd, library_path, load_library,
+)

@@ -1,0 +1,174 @@
+"""ctypes binding of ``libgws.so``: argument marshalling only.
+
+Function names and argument order mirror ``include/gws.h``.  torch is used for
+device memory and streams; every step of the method runs in the library's HIP
+kernels.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgws.so")
+
+FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
+
+EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_linear_fwd", "gws_gemm_bf16", "gws_noise_packed",
+           "gws_derive_seed", "gws_status_string", "gws_version")
+
+
+class GwsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+        self.status = status
+
+
+class _CTensor(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("w_hat", ctypes.c_void_p), ("bt", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("g", ctypes.c_void_p), ("dw", ctypes.c_void_p),
+                ("dbt", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("row0", ctypes.c_int64), ("col0", ctypes.c_int64),
+                ("seed", ctypes.c_uint64)]
+
+
+@dataclass
+class TensorDesc:
+    """Python-side mirror of ``gws_tensor``; tensor fields are torch device tensors or None."""
+    rows: int
+    cols: int
+    seed: int
+    w: Optional[object] = None
+    w_hat: Optional[object] = None
+    bt: Optional[object] = None
+    scale: Optional[object] = None
+    g: Optional[object] = None
+    dw: Optional[object] = None
+    dbt: Optional[object] = None
+    ld: Optional[int] = None
+    row0: int = 0
+    col0: int = 0
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libgws.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2505_11170_amd.build` "
+            "(hipcc, gfx950). There is no CPU or PyTorch fallback.")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, u64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+    tp = ctypes.POINTER(_CTensor)
+    L.gws_sample_fwd.argtypes = [tp, ci, ci, u64, vp]
+    L.gws_sample_fwd.restype = ci
+    L.gws_sample_bwd.argtypes = [tp, ci, u64, vp]
+    L.gws_sample_bwd.restype = ci
+    L.gws_linear_fwd.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
+    L.gws_linear_fwd.restype = ci
+    L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
+    L.gws_gemm_bf16.restype = ci
+    L.gws_noise_packed.argtypes = [vp, i64, i64, i64, i64, u64, u64, vp]
+    L.gws_noise_packed.restype = ci
+    L.gws_derive_seed.argtypes = [u64, u64]
+    L.gws_derive_seed.restype = u64
+    L.gws_status_string.argtypes = [ci]
+    L.gws_status_string.restype = ctypes.c_char_p
+    L.gws_version.argtypes = []
+    L.gws_version.restype = ci
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    try:
+        return load_library().gws_status_string(int(status)).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _p(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _marshal(descs: Sequence[TensorDesc]):
+    arr = (_CTensor * max(1, len(descs)))()
+    for c, d in zip(arr, descs):
+        ld = d.ld
+        if ld is None:
+            ref = d.w if d.w is not None else d.g
+            ld = int(ref.stride(0)) if ref is not None and ref.dim() == 2 else d.cols
+        c.w, c.w_hat, c.bt, c.scale = _p(d.w), _p(d.w_hat), _p(d.bt), _p(d.scale)
+        c.g, c.dw, c.dbt = _p(d.g), _p(d.dw), _p(d.dbt)
+        c.rows, c.cols, c.ld, c.row0, c.col0 = d.rows, d.cols, ld, d.row0, d.col0
+        c.seed = d.seed & (2 ** 64 - 1)
+    return arr
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise GwsError(rc, what)
+
+
+def gws_sample_fwd(t: Sequence[TensorDesc], fmt: int, step: int, stream=None) -> None:
+    """Paper Eq. 3 + cast for every descriptor; writes ``w_hat`` and ``scale``."""
+    L = load_library()
+    _check(L.gws_sample_fwd(_marshal(t), len(t), int(fmt), int(step), _stream(stream)), "gws_sample_fwd")
+
+
+def gws_sample_bwd(t: Sequence[TensorDesc], step: int, stream=None) -> None:
+    """Paper Eq. 4 for every descriptor; writes ``dbt`` (and ``dw`` unless aliased)."""
+    L = load_library()
+    _check(L.gws_sample_bwd(_marshal(t), len(t), int(step), _stream(stream)), "gws_sample_bwd")
+
+
+def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:
+    """Y = X * w_hat with the sampling fused into the GEMM's weight-operand path."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    _check(L.gws_linear_fwd(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt),
+                            int(step), _p(y), int(y.stride(0)), _stream(stream)), "gws_linear_fwd")
+
+
+def gws_gemm_bf16(x, w, y, w_is_nk: bool = False, stream=None) -> None:
+    """Plain BF16 GEMM twin of ``gws_linear_fwd`` (no sampling)."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    N = int(w.shape[0] if w_is_nk else w.shape[1])
+    _check(L.gws_gemm_bf16(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
+                           _p(y), int(y.stride(0)), _stream(stream)), "gws_gemm_bf16")
+
+
+def gws_noise_packed(out, rows: int, cols: int, seed: int, step: int, row0: int = 0, col0: int = 0,
+                     stream=None) -> None:
+    """Packed sign-magnitude noise codes, 8 per 32-bit word (paper Sec. 3.4)."""
+    L = load_library()
+    _check(L.gws_noise_packed(_p(out), rows, cols, row0, col0, seed & (2 ** 64 - 1), int(step),
+                              _stream(stream)), "gws_noise_packed")
+
+
+def gws_derive_seed(user_seed: int, tensor_id: int) -> int:
+    return int(load_library().gws_derive_seed(user_seed & (2 ** 64 - 1), tensor_id & (2 ** 64 - 1)))
+
+
+derive_seed = gws_derive_seed

@@ -1,0 +1,333 @@
+"""Pins of the oracle's forward (Eq. 3 + cast), backward (Eq. 4) and linear.
+
+The whole-pipeline checks recompose the forward from library routines (torch CPU
+bfloat16 / float8 arithmetic, numpy) on cases where every step is exactly
+defined by them (integer b_t makes 2^(1-b_t) an exact power of two), so a wrong
+block index, a transposed b_t, a dropped term or a wrong sign fails here.
+CPU only."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_11170_amd import synth
+
+LN2 = float(np.log(2.0))
+
+
+def bf16_val(bits):
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def to_bits(x):
+    """float array (values already BF16-representable or to be rounded RNE by torch) -> uint16."""
+    t = torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def block_absmax(wv, rows, cols):
+    nbr, nbc = oracle.n_blocks(rows, cols)
+    a = np.zeros((nbr, nbc))
+    for bi in range(nbr):
+        for bj in range(nbc):
+            a[bi, bj] = np.abs(wv[bi * 32:min(rows, bi * 32 + 32), bj * 32:min(cols, bj * 32 + 32)]).max()
+    return a
+
+
+def expand(blk, rows, cols):
+    return np.repeat(np.repeat(blk, 32, axis=0), 32, axis=1)[:rows, :cols]
+
+
+def library_forward(w_bits, bt_int, fmt, seed, step):
+    """Eq. 3 + cast recomposed from torch/numpy library arithmetic, integer b_t only."""
+    rows, cols = w_bits.shape
+    wv = bf16_val(w_bits)
+    a = block_absmax(wv, rows, cols)
+    s32 = (a * np.exp2(1.0 - bt_int)).astype(np.float32)          # exact: power-of-two factor
+    s16 = torch.from_numpy(s32).to(torch.bfloat16)                   # one rounding to BF16
+    r, _ = oracle.noise(rows, cols, seed, step)                      # R itself is pinned in test_oracle_rng
+    pqn = torch.from_numpy(r.astype(np.float32)).to(torch.bfloat16) * \
+        torch.from_numpy(expand(s16.float().numpy(), rows, cols)).to(torch.bfloat16)   # exact products
+    w_t = torch.from_numpy(w_bits.view(np.int16).copy()).view(torch.bfloat16)
+    w_hat = (w_t + pqn)                                              # torch BF16 add: one RNE
+    if fmt == oracle.FMT_BF16:
+        q = w_hat
+    else:
+        assert fmt == oracle.FMT_FP8_E4M3
+        Ea = np.floor(np.log2(a))
+        X = expand(np.exp2(Ea + 1 - 8), rows, cols).astype(np.float32)
+        y = w_hat.float() / torch.from_numpy(X)
+        assert (y.abs() <= 448).all()
+        q = (y.to(torch.float8_e4m3fn).float() * torch.from_numpy(X)).to(torch.bfloat16)
+    return q.view(torch.int16).numpy().view(np.uint16), s32
+
+
+@pytest.mark.parametrize("fmt", [oracle.FMT_BF16, oracle.FMT_FP8_E4M3])
+@pytest.mark.parametrize("shape", [(96, 160), (70, 45), (32, 32), (33, 257)])
+def test_forward_vs_library_composition(fmt, shape):
+    rows, cols = shape
+    t = synth.make_tensor(3, rows, cols, with_grad=False)
+    w = synth.bits(t["w"])
+    nbr, nbc = oracle.n_blocks(rows, cols)
+    # a different integer bitwidth per block, asymmetric in (row, col) so a transposed index shows
+    bt = (4 + (np.arange(nbr)[:, None] * 3 + np.arange(nbc)[None, :]) % 6).astype(np.float32)
+    seed, step = oracle.derive_seed(7, 3), 5
+    got, scale = oracle.sample_fwd(w, bt, fmt, seed, step)
+    want, s32 = library_forward(w, bt, fmt, seed, step)
+    assert (scale == s32).all()
+    assert (got == want).all(), np.argwhere(got != want)[:5]
+
+
+def test_forward_real_bt_scale_within_2ulp_of_fp64():
+    t = synth.make_tensor(1, 256, 256, with_grad=False)
+    w = synth.bits(t["w"])
+    bt = t["bt"].numpy()
+    _, scale = oracle.sample_fwd(w, bt, oracle.FMT_BF16, 1, 0)
+    a = block_absmax(bf16_val(w), 256, 256)
+    true = a * np.exp2(1.0 - bt.astype(np.float64))
+    ulp = np.spacing(true.astype(np.float32)).astype(np.float64)
+    assert (np.abs(scale.astype(np.float64) - true) <= 2 * ulp).all()
+    assert 4.0 <= bt.min() and bt.max() <= 9.0 and bt.std() > 1.0
+
+
+def _find(r, value, i_lim=32, j_lim=32):
+    pos = np.argwhere(r[:i_lim, :j_lim] == value)
+    assert len(pos), value
+    return pos
+
+
+def test_forward_hand_worked_block():
+    # one block, max|w| = 1.0, b_t = 4  =>  s = 0.125, X_e4m3 = 2^-7, X_e3m2 = 2^-3
+    seed, step = 99, 0
+    r, _ = oracle.noise(32, 32, seed, step)
+    cases = [  # (w, R, w_hat16, q_e4m3, q_e3m2)
+        (1.0, +2, 1.25, 1.25, 1.25),
+        (0.30078125, +1, 0.42578125, 0.4375, 0.4375),
+        (0.30078125, 0, 0.30078125, 0.3125, 0.3125),
+        (2.0 ** -7, -1, -0.1171875, -0.1171875, -0.125),
+        (2.0 ** -8, 0, 2.0 ** -8, 2.0 ** -8, 0.0),
+        (2.0 ** -17, 0, 2.0 ** -17, 0.0, 0.0),
+        (3 * 2.0 ** -18, 0, 3 * 2.0 ** -18, 2.0 ** -16, 0.0),
+        (-1.0, -2, -1.25, -1.25, -1.25),
+        (1.0, -1, 0.875, 0.875, 0.875),
+    ]
+    wv = np.zeros((32, 32))
+    used = set()
+    where = []
+    for (wval, rv, *_rest) in cases:
+        for (i, j) in _find(r, rv):
+            if (i, j) not in used:
+                used.add((i, j))
+                where.append((i, j))
+                wv[i, j] = wval
+                break
+    assert len(where) == len(cases)
+    w = to_bits(wv)
+    bt = np.full((1, 1), 4.0, dtype=np.float32)
+    outs = {f: bf16_val(oracle.sample_fwd(w, bt, f, seed, step)[0]) for f in (0, 1, 2)}
+    scale = oracle.sample_fwd(w, bt, 0, seed, step)[1]
+    assert scale[0, 0] == 0.125
+    for (i, j), (wval, rv, w16, q8, q6) in zip(where, cases):
+        assert outs[0][i, j] == w16, (wval, rv)
+        assert outs[1][i, j] == q8, (wval, rv)
+        assert outs[2][i, j] == q6, (wval, rv)
+    # elements left at w = 0 receive the bare PQN: R * 0.125
+    rest = np.ones((32, 32), dtype=bool)
+    for ij in where:
+        rest[ij] = False
+    assert (outs[0][rest] == (r.astype(np.float64) * 0.125)[rest]).all()
+
+
+def test_support_bound_and_prop4_precision_kept_where_r_is_zero():
+    rows, cols = 256, 320
+    t = synth.make_tensor(5, rows, cols, with_grad=False)
+    w = synth.bits(t["w"])
+    bt = t["bt"].numpy()
+    seed = oracle.derive_seed(0, 5)
+    r, _ = oracle.noise(rows, cols, seed, 2)
+    wv = bf16_val(w)
+    for fmt in (0, 1, 2):
+        q, scale = oracle.sample_fwd(w, bt, fmt, seed, 2)
+        qv = bf16_val(q)
+        s = expand(bf16_val(to_bits(scale)), rows, cols)
+        # R in {0, +-1, +-2}: |w_hat - w| <= 2 s (+ rounding: half an ulp of BF16, or of the coarser target)
+        a = expand(block_absmax(wv, rows, cols), rows, cols)
+        m = {0: 7, 1: 3, 2: 2}[fmt]
+        half_ulp = 2.0 ** (np.floor(np.log2(a)) + 1 - m) / 2
+        assert (np.abs(qv - wv) <= 2 * s + half_ulp).all()
+        # Prop. 4: where R = 0 the result is exactly cast(w)
+        q0, _ = oracle.sample_fwd(w, np.full_like(bt, 60.0), fmt, seed, 2)     # b_t = 60: PQN below any ulp
+        z = r == 0
+        assert (qv[z] == bf16_val(q0)[z]).all()
+        if fmt == 0:
+            assert (qv[z] == wv[z]).all()
+    assert abs((r == 0).mean() - 0.7166443) < 5 * np.sqrt(0.7166 * 0.2834 / r.size)
+
+
+@pytest.mark.parametrize("fmt,m,btmax", [(oracle.FMT_BF16, 7, 8), (oracle.FMT_FP8_E4M3, 3, 4), (oracle.FMT_FP6_E3M2, 2, 3)])
+def test_lemma1_pqn_does_not_underflow(fmt, m, btmax):
+    # Eq. 5 / Lemma 1 (tau = 0): for b_t <= m + 1 every element with R != 0 differs from
+    # its un-noised cast, provided w itself is representable in the target format.
+    rows = cols = 256
+    t = synth.make_tensor(9, rows, cols, with_grad=False)
+    w0 = synth.bits(t["w"])
+    big = np.full((8, 8), 60.0, dtype=np.float32)
+    # cast only (b_t = 60 puts the noise far below any ulp); repeated until stable because
+    # rounding max|w| up into the next binade moves the block's subnormal threshold
+    w_on_grid = w0
+    for _ in range(4):
+        prev = w_on_grid
+        w_on_grid, _ = oracle.sample_fwd(prev, big, fmt, 1, 0)
+    assert (bf16_val(w_on_grid) == bf16_val(prev)).all()
+    r, _ = oracle.noise(rows, cols, 77, 1)
+    for bt_val in (btmax, btmax - 1.0, btmax - 0.37):
+        bt = np.full((8, 8), bt_val, dtype=np.float32)
+        q, _ = oracle.sample_fwd(w_on_grid, bt, fmt, 77, 1)
+        nz = r != 0
+        assert (bf16_val(q)[nz] != bf16_val(w_on_grid)[nz]).all()
+        assert (q[~nz] == w_on_grid[~nz]).all() or (bf16_val(q)[~nz] == bf16_val(w_on_grid)[~nz]).all()
+
+
+def test_bt9_tie_erases_noise_on_bf16():
+    # why the bound of Lemma 1 is strict: at b_t = 9, 1.0 + 2^-8 rounds back to 1.0
+    r, _ = oracle.noise(32, 32, 4, 0)
+    (i, j) = _find(r, 1)[0]
+    wv = np.zeros((32, 32))
+    wv[0, 0] = 1.0 if (i, j) != (0, 0) else 0.0
+    wv[i, j] = 1.0
+    q, scale = oracle.sample_fwd(to_bits(wv), np.full((1, 1), 9.0, np.float32), 0, 4, 0)
+    assert scale[0, 0] == 2.0 ** -8
+    assert bf16_val(q)[i, j] == 1.0
+
+
+def test_table_c1_formulas():
+    # Sec. 3.3 with tau = 0: exponent bits ceil(log2(b_t+1)) for w, ceil(log2(b_t+3)) for
+    # w_hat, mantissa b_t - 2; must reproduce every printed row of Table C.1.
+    path = os.path.join(os.path.dirname(__file__), "golden", "table_c1.txt")
+    rows = [list(map(int, l.split())) for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 11
+    for bt, ew, e, m in rows:
+        assert ew == int(np.ceil(np.log2(bt + 1)))
+        assert e == int(np.ceil(np.log2(bt + 3)))
+        assert m == bt - 2
+
+
+def test_all_zero_block_and_negative_zero():
+    w = np.zeros((32, 64), dtype=np.uint16)
+    w[:, 32:] = to_bits(np.full((32, 32), 0.5))
+    w[3, 5] = 0x8000
+    q, scale = oracle.sample_fwd(w, np.full((1, 2), 5.0, np.float32), 1, 3, 3)
+    assert scale[0, 0] == 0.0 and scale[0, 1] == 0.5 * 2.0 ** -4
+    assert (bf16_val(q)[:, :32] == 0).all()
+    _, packed = oracle.noise(32, 64, 3, 3)
+    code = (int(packed[3, 0]) >> 20) & 0xF
+    # -0 + (+-0): sign-magnitude PQN keeps its sign bit, IEEE add decides
+    assert q[3, 5] == (0x8000 if code & 8 else 0x0000)
+
+
+def test_edge_blocks_and_row_padding():
+    rows, cols, ld = 45, 70, 72
+    t = synth.make_tensor(2, rows, cols, with_grad=True, ld=ld)
+    w = synth.bits(t["w"])
+    bt = np.full(oracle.n_blocks(rows, cols), 5.0, dtype=np.float32)
+    q, scale = oracle.sample_fwd(w, bt, 0, 8, 1, cols=cols)
+    assert (q[:, cols:] == w[:, cols:]).all()                 # padding untouched
+    a = block_absmax(bf16_val(w)[:, :cols], rows, cols)       # max over existing elements only
+    assert (scale == (a * 2.0 ** -4).astype(np.float32)).all()
+    # identical to running on the compact tensor: the counter does not depend on ld
+    q2, _ = oracle.sample_fwd(np.ascontiguousarray(w[:, :cols]), bt, 0, 8, 1)
+    assert (q2 == q[:, :cols]).all()
+
+
+# ---------------------------------------------------------------- backward (Eq. 4)
+def test_backward_dw_is_g_and_dbt_matches_definition():
+    rows, cols = 96, 128
+    t = synth.make_tensor(4, rows, cols)
+    w, g, bt = synth.bits(t["w"]), synth.bits(t["g"]), t["bt"].numpy()
+    seed = oracle.derive_seed(0, 4)
+    _, scale = oracle.sample_fwd(w, bt, 1, seed, 6)
+    dw, dbt, asum = oracle.sample_bwd(g, scale, seed, 6)
+    assert (dw == g).all()
+    r, _ = oracle.noise(rows, cols, seed, 6)
+    gr = bf16_val(g) * r
+    for bi in range(3):
+        for bj in range(4):
+            acc = gr[bi * 32:bi * 32 + 32, bj * 32:bj * 32 + 32].sum()
+            assert np.isclose(dbt[bi, bj], -LN2 * float(scale[bi, bj]) * acc, rtol=1e-12, atol=0)
+            assert np.isclose(asum[bi, bj], LN2 * float(scale[bi, bj]) *
+                              np.abs(gr[bi * 32:bi * 32 + 32, bj * 32:bj * 32 + 32]).sum(), rtol=1e-12)
+
+
+def test_backward_matches_finite_difference_of_eq3():
+    # L(b_t) = sum(g .* w_hat(b_t)) on the real-valued Eq. 3 with R held fixed
+    rows, cols = 64, 96
+    t = synth.make_tensor(6, rows, cols)
+    w, g, bt = synth.bits(t["w"]), synth.bits(t["g"]), t["bt"].numpy().astype(np.float64)
+    seed = 1234
+    r, _ = oracle.noise(rows, cols, seed, 0)
+    wv, gv = bf16_val(w), bf16_val(g)
+    a = block_absmax(wv, rows, cols)
+
+    def loss_blocks(b):
+        w_hat = wv + r * expand(a * np.exp2(1.0 - b), rows, cols)
+        prod = gv * w_hat
+        return prod.reshape(2, 32, 3, 32).sum(axis=(1, 3))
+    h = 1e-4
+    fd = (loss_blocks(bt + h) - loss_blocks(bt - h)) / (2 * h)
+    _, scale = oracle.sample_fwd(w, bt.astype(np.float32), 0, seed, 0)
+    _, dbt, asum = oracle.sample_bwd(g, scale, seed, 0)
+    assert np.allclose(dbt, fd, rtol=2e-6, atol=1e-7 * asum.max())
+    assert (np.sign(dbt) == np.sign(fd)).all()
+
+
+def test_backward_linearity_and_integer_case():
+    rows = cols = 64
+    seed, step = 21, 2
+    r, _ = oracle.noise(rows, cols, seed, step)
+    scale = np.array([[0.5, 0.25], [1.0, 2.0]], dtype=np.float32)
+    g_r = to_bits(r.astype(np.float32))                       # g = R  =>  sum g.R = sum R^2 (an integer)
+    _, dbt, _ = oracle.sample_bwd(g_r, scale, seed, step)
+    r2 = (r.astype(np.int64) ** 2).reshape(2, 32, 2, 32).sum(axis=(1, 3))
+    assert np.allclose(dbt, -LN2 * scale.astype(np.float64) * r2, rtol=1e-15, atol=0)
+    t = synth.make_tensor(8, rows, cols)
+    g1 = synth.bits(t["g"])
+    g2 = to_bits(bf16_val(g1) * 4.0)                          # exact scaling
+    d1 = oracle.sample_bwd(g1, scale, seed, step)[1]
+    d2 = oracle.sample_bwd(g2, scale, seed, step)[1]
+    assert np.allclose(d2, 4 * d1, rtol=1e-15, atol=0)
+    # a different step gives a different R, hence a different gradient
+    d3 = oracle.sample_bwd(g1, scale, seed, step + 1)[1]
+    assert not np.allclose(d3, d1)
+
+
+def test_backward_edge_blocks():
+    rows, cols, ld = 40, 50, 56
+    t = synth.make_tensor(10, rows, cols, ld=ld)
+    g = synth.bits(t["g"])
+    scale = np.ones(oracle.n_blocks(rows, cols), dtype=np.float32)
+    dw, dbt, _ = oracle.sample_bwd(g, scale, 5, 5, cols=cols)
+    assert (dw[:, :cols] == g[:, :cols]).all() and (dw[:, cols:] == 0).all()
+    r, _ = oracle.noise(rows, cols, 5, 5)
+    gr = bf16_val(g)[:, :cols] * r
+    assert np.isclose(dbt[1, 1], -LN2 * gr[32:, 32:].sum(), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- linear
+def test_linear_vs_numpy_fp64_matmul():
+    rng = np.random.default_rng(0)
+    M, K, N = 37, 96, 50
+    x = to_bits(rng.standard_normal((M, K)))
+    q = to_bits(rng.standard_normal((K, N)) * 0.02)
+    y64, yabs, y16 = oracle.linear_fwd(x, q)
+    ref = bf16_val(x) @ bf16_val(q)
+    assert np.allclose(y64, ref, rtol=1e-12, atol=1e-15)
+    assert np.allclose(yabs, np.abs(bf16_val(x)) @ np.abs(bf16_val(q)), rtol=1e-12)
+    want16 = torch.from_numpy(ref).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (y16 == want16).mean() > 0.999                       # fp64 summation order may flip a rare tie
+    # [N x K] storage and row selection
+    qt = np.ascontiguousarray(q.T)
+    y64b, _, _ = oracle.linear_fwd(x, qt, w_is_nk=True, rows_sel=[5, 0, 36])
+    assert np.allclose(y64b, ref[[5, 0, 36]], rtol=1e-12, atol=1e-15)
