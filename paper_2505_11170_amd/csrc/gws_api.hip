@@ -1,0 +1,213 @@
+// C ABI of libgws: argument validation and launch planning.  Declarations and
+// the meaning of every argument are in include/gws.h.
+#include <string.h>
+
+#include "gws_launch.h"
+
+namespace {
+
+using namespace gws;
+
+inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Shape rules common to forward and backward.
+int check_shape(const gws_tensor& t) {
+  if (t.rows < 0 || t.cols < 0 || t.ld < 0) return GWS_ERR_SHAPE;
+  if (t.rows >= (int64_t)1 << 31 || t.cols >= (int64_t)1 << 31 || t.ld >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (t.rows == 0 || t.cols == 0) return GWS_OK;
+  if (t.ld < t.cols || (t.ld & 7) != 0) return GWS_ERR_SHAPE;
+  if (t.row0 < 0 || t.col0 < 0 || (t.row0 & 31) != 0 || (t.col0 & 31) != 0) return GWS_ERR_SHAPE;
+  if (t.row0 + t.rows > (int64_t)0xFFFFFFFFll || (t.col0 + t.cols) / 8 > (int64_t)0xFFFFFFFFll) return GWS_ERR_SHAPE;
+  return GWS_OK;
+}
+
+inline bool overlap(const void* a, const void* b, size_t bytes) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + bytes && y < x + bytes;
+}
+
+int check_fwd(const gws_tensor& t) {
+  int rc = check_shape(t);
+  if (rc != GWS_OK || t.rows == 0 || t.cols == 0) return rc;
+  if (!t.w || !t.w_hat || !t.bt || !t.scale) return GWS_ERR_NULL;
+  if (!aligned(t.w, 16) || !aligned(t.w_hat, 16) || !aligned(t.bt, 4) || !aligned(t.scale, 4)) return GWS_ERR_ALIGN;
+  if (overlap(t.w, t.w_hat, (size_t)t.rows * t.ld * 2)) return GWS_ERR_ALIAS;
+  return GWS_OK;
+}
+
+int check_bwd(const gws_tensor& t) {
+  int rc = check_shape(t);
+  if (rc != GWS_OK || t.rows == 0 || t.cols == 0) return rc;
+  if (!t.g || !t.dbt || !t.scale) return GWS_ERR_NULL;
+  if (!aligned(t.g, 16) || !aligned(t.dw, 16) || !aligned(t.dbt, 4) || !aligned(t.scale, 4)) return GWS_ERR_ALIGN;
+  if (t.dw && t.dw != t.g && overlap(t.g, t.dw, (size_t)t.rows * t.ld * 2)) return GWS_ERR_ALIAS;
+  return GWS_OK;
+}
+
+void fill_common(TileDesc& d, const gws_tensor& t, uint32_t tile_begin) {
+  d.rows = (uint32_t)t.rows;
+  d.cols = (uint32_t)t.cols;
+  d.ld = (uint32_t)t.ld;
+  d.row0 = (uint32_t)t.row0;
+  d.cg0 = (uint32_t)(t.col0 / 8);
+  d.seed_lo = (uint32_t)t.seed;
+  d.seed_hi = (uint32_t)(t.seed >> 32);
+  d.tile_begin = tile_begin;
+  d.tiles_x = (uint32_t)((t.cols + kTileCols - 1) / kTileCols);
+  d.pad_ = 0;
+}
+
+inline uint64_t tile_count(const gws_tensor& t) {
+  return (uint64_t)((t.rows + 31) / 32) * (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
+}
+
+// Pack descriptors into as few launches as the kernel-argument segment and the
+// 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
+int run_batched(const gws_tensor* t, int n, bool fwd, int fmt, uint64_t step, hipStream_t stream) {
+  LaunchArgs a;
+  memset(&a, 0, sizeof a);
+  a.step_lo = (uint32_t)step;
+  a.step_hi = (uint32_t)(step >> 32);
+  uint64_t tiles = 0;
+  auto flush = [&]() -> int {
+    if (a.n == 0) return GWS_OK;
+    int rc = fwd ? launch_sample_fwd(a, (uint32_t)tiles, fmt, stream) : launch_sample_bwd(a, (uint32_t)tiles, stream);
+    a.n = 0;
+    tiles = 0;
+    return rc;
+  };
+  for (int i = 0; i < n; ++i) {
+    if (t[i].rows == 0 || t[i].cols == 0) continue;
+    const uint64_t tc = tile_count(t[i]);
+    if (tc >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
+    if (a.n == (uint32_t)kMaxTensorsPerLaunch || tiles + tc >= 0x7FFFFFFFull) {
+      int rc = flush();
+      if (rc != GWS_OK) return rc;
+    }
+    TileDesc& d = a.t[a.n++];
+    if (fwd) {
+      d.p0 = t[i].w; d.p1 = t[i].w_hat; d.p2 = (void*)t[i].bt; d.p3 = t[i].scale;
+    } else {
+      d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
+    }
+    fill_common(d, t[i], (uint32_t)tiles);
+    tiles += tc;
+  }
+  return flush();
+}
+
+}  // namespace
+
+extern "C" {
+
+int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_fwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, true, fmt, step, (hipStream_t)stream);
+}
+
+int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_bwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, false, 0, step, (hipStream_t)stream);
+}
+
+int gws_noise_packed(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0,
+                     uint64_t seed, uint64_t step, void* stream) {
+  if (rows < 0 || cols < 0 || row0 < 0 || col0 < 0 || (col0 & 7) != 0) return GWS_ERR_SHAPE;
+  if (rows + row0 > (int64_t)0xFFFFFFFFll || (cols + col0) / 8 > (int64_t)0xFFFFFFFFll) return GWS_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return GWS_OK;
+  if (!out) return GWS_ERR_NULL;
+  if (!aligned(out, 4)) return GWS_ERR_ALIGN;
+  const int64_t ngrp = (cols + 7) / 8;
+  if ((uint64_t)rows * (uint64_t)ngrp >= ((uint64_t)1 << 39)) return GWS_ERR_SHAPE;
+  return launch_noise_packed((uint32_t*)out, (uint32_t)rows, (uint32_t)ngrp, (uint32_t)row0,
+                             (uint32_t)(col0 / 8), seed, step, (hipStream_t)stream);
+}
+
+int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
+                   int fmt, uint64_t step, void* y, int64_t ldy, void* stream) {
+  if (!w) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  int rc = check_shape(*w);
+  if (rc != GWS_OK) return rc;
+  const int64_t Kw = w_is_nk ? w->cols : w->rows, N = w_is_nk ? w->rows : w->cols;
+  if (M < 0 || K < 0 || K != Kw || M >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (M == 0 || N == 0) return GWS_OK;
+  if ((K & 31) != 0 || (N & 31) != 0 || K == 0) return GWS_ERR_SHAPE;
+  if (ldx < K || ldy < N || (ldx & 7) != 0 || (ldy & 7) != 0 || ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (!x || !y || !w->w || !w->bt) return GWS_ERR_NULL;
+  if ((w->w_hat == nullptr) != (w->scale == nullptr)) return GWS_ERR_NULL;
+  if (!aligned(x, 16) || !aligned(y, 16) || !aligned(w->w, 16) || !aligned(w->w_hat, 16) ||
+      !aligned(w->bt, 4) || !aligned(w->scale, 4)) return GWS_ERR_ALIGN;
+  if (w->w_hat && overlap(w->w, w->w_hat, (size_t)w->rows * w->ld * 2)) return GWS_ERR_ALIAS;
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.x = (const uint16_t*)x; g.w = (const uint16_t*)w->w; g.y = (uint16_t*)y;
+  g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
+  g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)w->ld; g.ldy = (uint32_t)ldy;
+  g.bt = w->bt; g.scale = w->scale; g.w_hat = (uint16_t*)w->w_hat;
+  g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
+  g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
+  g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
+  return launch_gemm(g, w_is_nk, 1, fmt, (hipStream_t)stream);
+}
+
+int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                  int w_is_nk, void* y, int64_t ldy, void* stream) {
+  if (M < 0 || K < 0 || N < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (M == 0 || N == 0) return GWS_OK;
+  if ((K & 31) != 0 || (N & 31) != 0 || K == 0) return GWS_ERR_SHAPE;
+  const int64_t wcols = w_is_nk ? K : N;
+  if (ldx < K || ldy < N || ldw < wcols || ((ldx | ldy | ldw) & 7) != 0 ||
+      ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31 || ldw >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (!x || !w || !y) return GWS_ERR_NULL;
+  if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return GWS_ERR_ALIGN;
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.x = (const uint16_t*)x; g.w = (const uint16_t*)w; g.y = (uint16_t*)y;
+  g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
+  g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)ldw; g.ldy = (uint32_t)ldy;
+  return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+}
+
+// Philox4x32-10 on the host, for the seed derivation only.
+uint64_t gws_derive_seed(uint64_t user_seed, uint64_t tensor_id) {
+  uint32_t c0 = (uint32_t)tensor_id, c1 = (uint32_t)(tensor_id >> 32), c2 = 0x47575331u, c3 = 0u;
+  uint32_t k0 = (uint32_t)user_seed, k1 = (uint32_t)(user_seed >> 32);
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  return (uint64_t)c0 | ((uint64_t)c1 << 32);
+}
+
+const char* gws_status_string(int status) {
+  switch (status) {
+    case GWS_OK: return "ok";
+    case GWS_ERR_NULL: return "required pointer is NULL";
+    case GWS_ERR_SHAPE: return "invalid shape, leading dimension or shard origin";
+    case GWS_ERR_ALIGN: return "misaligned pointer";
+    case GWS_ERR_FORMAT: return "unknown target format";
+    case GWS_ERR_LAUNCH: return "kernel launch failed";
+    case GWS_ERR_ALIAS: return "output overlaps input";
+    default: return "unknown status";
+  }
+}
+
+int gws_version(void) { return 1; }
+
+}  // extern "C"

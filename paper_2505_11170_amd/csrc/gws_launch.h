@@ -1,0 +1,60 @@
+// Launch descriptors shared by the host API and the kernels (internal to csrc/).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gws.h"
+#include "gws_device.h"
+
+namespace gws {
+
+constexpr int kThreads = 256;       // 4 wavefronts per workgroup
+constexpr int kTileCols = 256;      // a workgroup covers 32 rows x 256 columns
+constexpr int kMaxTensorsPerLaunch = 40;
+
+// One tensor as a kernel sees it.  p0..p3 are, for the forward pass,
+// (w, w_hat, bt, scale) and, for the backward pass, (g, dw-or-NULL, dbt, scale).
+struct TileDesc {
+  const void* p0;
+  void* p1;
+  void* p2;
+  void* p3;
+  uint32_t rows, cols, ld;
+  uint32_t row0, cg0;          // shard origin: row offset, column-group (col0 / 8) offset
+  uint32_t seed_lo, seed_hi;
+  uint32_t tile_begin;         // first workgroup of this tensor within the launch
+  uint32_t tiles_x;            // workgroup tiles per block row = ceil(cols / 256)
+  uint32_t pad_;
+};
+
+// Passed by value: lives in the kernel-argument segment (at most 4 KiB).
+struct LaunchArgs {
+  TileDesc t[kMaxTensorsPerLaunch];
+  uint32_t n;
+  uint32_t step_lo, step_hi;
+  uint32_t pad_;
+};
+static_assert(sizeof(LaunchArgs) <= 3968, "kernel arguments must fit the 4 KiB segment");
+
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_tiles, int fmt, hipStream_t stream);
+int launch_sample_bwd(const LaunchArgs& a, uint32_t n_tiles, hipStream_t stream);
+int launch_noise_packed(uint32_t* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0,
+                        uint64_t seed, uint64_t step, hipStream_t stream);
+
+// GEMM launchers (gws_linear.hip)
+struct GemmArgs {
+  const uint16_t* x;   // [M x K], ldx
+  const uint16_t* w;   // [K x N] or [N x K], ldw
+  uint16_t* y;         // [M x N], ldy
+  uint32_t M, N, K;
+  uint32_t ldx, ldw, ldy;
+  // sampling (fused variant only)
+  const float* bt;
+  float* scale;        // may be NULL
+  uint16_t* w_hat;     // may be NULL
+  uint32_t row0, cg0, seed_lo, seed_hi, step_lo, step_hi;
+};
+int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
+
+}  // namespace gws

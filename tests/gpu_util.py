@@ -1,0 +1,79 @@
+"""Helpers of the GPU parity tests: run the HIP path through the C ABI binding and
+the oracle on the same seeded inputs, compare element by element."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2505_11170_amd as gws
+from paper_2505_11170_amd import synth
+
+DEV = "cuda:0"
+
+
+def ensure_built():
+    import os
+    from paper_2505_11170_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2505_11170_amd.build import build_library
+        build_library()
+    gws.load_library()
+
+
+def dev(t):
+    return None if t is None else t.to(DEV)
+
+
+def gpu_forward(items, fmt, step):
+    """items: list of dict(w, bt, rows, cols, seed[, row0, col0]) with CPU or GPU tensors.
+    Returns list of (w_hat uint16 ndarray [rows, ld], scale float32 ndarray)."""
+    descs, keep = [], []
+    for it in items:
+        w = dev(it["w"]).contiguous()
+        bt = dev(it["bt"]).contiguous()
+        w_hat = w.clone()          # so that padding columns can be checked for "never written"
+        nbr, nbc = synth.n_blocks(it["rows"], it["cols"])
+        scale = torch.full((nbr, nbc), float("nan"), device=DEV, dtype=torch.float32)
+        descs.append(gws.TensorDesc(rows=it["rows"], cols=it["cols"], seed=it["seed"], w=w, w_hat=w_hat, bt=bt,
+                                    scale=scale, ld=(w.stride(0) if w.dim() == 2 and w.numel() else it["cols"]),
+                                    row0=it.get("row0", 0), col0=it.get("col0", 0)))
+        keep.append((w, bt, w_hat, scale))
+    gws.gws_sample_fwd(descs, fmt, step)
+    torch.cuda.synchronize()
+    return [(synth.bits(k[2]), k[3].cpu().numpy()) for k in keep], keep
+
+
+def gpu_backward(items, step, dw_mode="copy"):
+    """items: dict(g, scale, rows, cols, seed).  dw_mode: 'copy' | 'none' | 'alias'."""
+    descs, keep = [], []
+    for it in items:
+        g = dev(it["g"]).contiguous()
+        scale = dev(torch.as_tensor(it["scale"])).contiguous()
+        nbr, nbc = synth.n_blocks(it["rows"], it["cols"])
+        dbt = torch.full((nbr, nbc), float("nan"), device=DEV, dtype=torch.float32)
+        dw = None
+        if dw_mode == "copy":
+            dw = torch.zeros_like(g)
+        elif dw_mode == "alias":
+            dw = g
+        descs.append(gws.TensorDesc(rows=it["rows"], cols=it["cols"], seed=it["seed"], g=g, dw=dw, dbt=dbt,
+                                    scale=scale, ld=(g.stride(0) if g.dim() == 2 and g.numel() else it["cols"]),
+                                    row0=it.get("row0", 0), col0=it.get("col0", 0)))
+        keep.append((g, scale, dw, dbt))
+    gws.gws_sample_bwd(descs, step)
+    torch.cuda.synchronize()
+    out = []
+    for k in keep:
+        out.append((None if k[2] is None else synth.bits(k[2]), k[3].cpu().numpy()))
+    return out, keep
+
+
+def assert_dbt_close(got, ref, abs_sum, what=""):
+    """Spec tolerance for the per-block gradient: 1e-5 relative, plus the rounding
+    floor of a 1024-term fp32 sum when the +- terms cancel (1e-6 of sum|terms|)."""
+    got = got.astype(np.float64)
+    err = np.abs(got - ref)
+    tol_rel = 1e-5 * np.abs(ref)
+    tol = tol_rel + 1e-6 * abs_sum
+    bad = err > tol
+    assert not bad.any(), (what, np.argwhere(bad)[:5], err[bad][:5], tol[bad][:5])
+    return int((err > tol_rel).sum())   # blocks that needed the cancellation term

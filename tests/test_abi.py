@@ -1,0 +1,97 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol that
+include/gws.h declares, validates arguments before any launch, and derives seeds
+like the oracle.  No GPU work is issued here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2505_11170_amd import binding
+from paper_2505_11170_amd.binding import _CTensor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        from paper_2505_11170_amd.build import build_library
+        build_library()
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gws.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gws_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"gws_sample_fwd", "gws_sample_bwd", "gws_linear_fwd"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+    assert lib.gws_version() >= 1
+
+
+def test_derive_seed_matches_oracle(lib):
+    for u, t in [(0, 0), (0, 1), (1, 0), (0xDEADBEEF12345678, 0x1_00000002), (2 ** 64 - 1, 2 ** 64 - 1)]:
+        assert binding.gws_derive_seed(u, t) == oracle.derive_seed(u, t)
+
+
+def _t(**kw):
+    c = _CTensor()
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_argument_validation_launches_nothing(lib):
+    OK, NULL, SHAPE, ALIGN, FORMAT, LAUNCH, ALIAS = range(7)
+    fake = 0x10000  # never dereferenced: every case below fails validation first
+    base = dict(w=fake, w_hat=fake + 0x100000, bt=fake, scale=fake, g=fake, dw=None, dbt=fake,
+                rows=64, cols=64, ld=64, row0=0, col0=0, seed=1)
+
+    def fwd(fmt=1, **over):
+        arr = (_CTensor * 1)(_t(**{**base, **over}))
+        return lib.gws_sample_fwd(arr, 1, fmt, 0, None)
+
+    def bwd(**over):
+        arr = (_CTensor * 1)(_t(**{**base, **over}))
+        return lib.gws_sample_bwd(arr, 1, 0, None)
+
+    assert lib.gws_sample_fwd(None, 0, 1, 0, None) == OK          # empty list
+    assert lib.gws_sample_fwd(None, 1, 1, 0, None) == NULL
+    assert lib.gws_sample_fwd(None, -1, 1, 0, None) == SHAPE
+    assert fwd(rows=0) == OK and fwd(cols=0) == OK and bwd(rows=0) == OK   # empty tensors are skipped
+    assert fwd(w=None) == NULL and fwd(w_hat=None) == NULL and fwd(bt=None) == NULL and fwd(scale=None) == NULL
+    assert fwd(fmt=3) == FORMAT and fwd(fmt=-1) == FORMAT
+    assert fwd(ld=60) == SHAPE and fwd(ld=56) == SHAPE and fwd(rows=-1) == SHAPE and fwd(cols=2 ** 31) == SHAPE
+    assert fwd(row0=16) == SHAPE and fwd(col0=8) == SHAPE and fwd(row0=-32) == SHAPE
+    assert fwd(w=fake + 2) == ALIGN and fwd(w_hat=fake + 0x100008) == ALIGN and fwd(bt=fake + 1) == ALIGN
+    assert fwd(w_hat=fake) == ALIAS and fwd(w_hat=fake + 64) == ALIAS
+    assert bwd(g=None) == NULL and bwd(dbt=None) == NULL and bwd(scale=None) == NULL
+    assert bwd(g=fake + 4) == ALIGN and bwd(dw=fake + 32) == ALIAS
+    assert bwd(ld=63) == SHAPE
+    assert lib.gws_noise_packed(None, 4, 4, 0, 0, 0, 0, None) == NULL
+    assert lib.gws_noise_packed(fake, 4, 4, 0, 4, 0, 0, None) == SHAPE
+    assert lib.gws_noise_packed(None, 0, 4, 0, 0, 0, 0, None) == OK
+    # linear: shape rules
+    wdesc = (_CTensor * 1)(_t(**base))
+    assert lib.gws_linear_fwd(fake, 8, 32, 32, wdesc, 0, 1, 0, fake, 64, None) == SHAPE      # K mismatch
+    assert lib.gws_linear_fwd(fake, 8, 64, 64, wdesc, 0, 9, 0, fake, 64, None) == FORMAT
+    assert lib.gws_gemm_bf16(fake, 8, 48, 48, fake, 64, 64, 0, fake, 64, None) == SHAPE      # K % 32
+    assert lib.gws_gemm_bf16(None, 8, 64, 64, fake, 64, 64, 0, fake, 64, None) == NULL
+    assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty
+    for s in range(7):
+        assert lib.gws_status_string(s)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libgws.so"))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.load_library()
