@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the GaussWS hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt2_124m|llama_1b]
+
+A step is one pass of the whole hot path over every linear weight of the workload:
+gws_sample_fwd (paper Eq. 3 + FP8-E4M3 cast) followed by gws_sample_bwd (Eq. 4, dL/dw
+passed through as an alias).  Inputs are seeded synthetic tensors already resident in
+HBM.  The last line printed is one JSON object (metric, roofline, cpu_baseline, extras).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense BF16, published
+FWD_BYTES_PER_PARAM = 4.0      # read w (2) + write w_hat (2); + 8 B per 1024-param block (b_t, scale)
+BWD_BYTES_PER_PARAM = 2.0      # read dL/dw_hat (2); dL/dw aliased; + 8 B per block (scale, db_t)
+BLOCK_BYTES = 8.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt2_124m", choices=["gpt2_124m", "llama_1b"])
+    ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets rotated through (0 = auto)")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the GaussWS hot path needs no exchange "
+              "between GPUs; see DESIGN.md, 'More than one GPU'). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_11170_amd as gws
+    from paper_2505_11170_amd import binding, synth
+
+    if not os.path.exists(binding.library_path()):
+        from paper_2505_11170_amd.build import build_library
+        build_library()
+    gws.load_library()
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU: the HIP path has no fallback")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def make_sets(shapes, n_sets, bt=None):
+        """n_sets independent copies of (W, w_hat, b_t, scale, g, db_t) for every shape."""
+        sets = []
+        idx = 0
+        for s in range(n_sets):
+            descs = []
+            for i, sh in enumerate(shapes):
+                t = synth.make_tensor(idx, sh.rows, sh.cols, bt=bt, device=dev)
+                idx += 1
+                nbr, nbc = synth.n_blocks(sh.rows, sh.cols)
+                descs.append(gws.TensorDesc(
+                    rows=sh.rows, cols=sh.cols, seed=gws.gws_derive_seed(0, i), w=t["w"], w_hat=torch.empty_like(t["w"]),
+                    bt=t["bt"], scale=torch.empty(nbr, nbc, device=dev), g=t["g"], dw=t["g"],
+                    dbt=torch.empty(nbr, nbc, device=dev)))
+            sets.append((descs, gws.pack(descs)))
+        return sets
+
+    def run_workload(shapes, steps, warmup, n_sets, fmt=gws.FMT_FP8_E4M3, bt=None):
+        params = sum(s.rows * s.cols for s in shapes)
+        blocks = sum(synth.n_blocks(s.rows, s.cols)[0] * synth.n_blocks(s.rows, s.cols)[1] for s in shapes)
+        sets = make_sets(shapes, n_sets, bt=bt)
+        n_launch = (len(shapes) + 53) // 54
+        for s in range(warmup):
+            _, p = sets[s % n_sets]
+            gws.gws_sample_fwd(p, fmt, s)
+            gws.gws_sample_bwd(p, s)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            _, p = sets[s % n_sets]
+            ev[s][0].record()
+            gws.gws_sample_fwd(p, fmt, warmup + s)
+            ev[s][1].record()
+            gws.gws_sample_bwd(p, warmup + s)
+            ev[s][2].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+        bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+        return dict(params=params, blocks=blocks, n_launch=n_launch, wall_s=t1 - t0, fwd_ms=fwd_ms, bwd_ms=bwd_ms,
+                    sets=sets)
+
+    shapes = synth.gpt2_124m_shapes() if args.workload == "gpt2_124m" else synth.llama_1b_shapes()
+    params = sum(s.rows * s.cols for s in shapes)
+    # Rotate through enough distinct buffer sets that no operand can still sit in the 256 MB
+    # last-level cache when it is touched again (each set is 6 bytes per parameter per step).
+    n_sets = args.sets or max(1, min(8, int(1.5e9 // (6 * params)) + 1))
+    res = run_workload(shapes, args.steps, args.warmup, n_sets)
+    ms_per_step = res["wall_s"] * 1e3 / args.steps
+    value = params * args.steps / res["wall_s"]
+    fwd_bytes = FWD_BYTES_PER_PARAM * params + BLOCK_BYTES * res["blocks"]
+    bwd_bytes = BWD_BYTES_PER_PARAM * params + BLOCK_BYTES * res["blocks"]
+    fwd_launch_ms = res["fwd_ms"] / res["n_launch"]
+    achieved = (fwd_bytes / res["n_launch"]) / (fwd_launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "GaussWS fwd+bwd sampled params/s",
+        "value": value,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: all {len(shapes)} linear weights, {params} params, W~N(0,0.02) BF16, "
+                               "b_t~U[4,9] per 32x32 block, dW~N(0,1e-3), FP8-E4M3 cast, fwd+bwd (dW aliased), "
+                               f"{n_sets} buffer sets rotated",
+                   "params": params, "buffer_sets": n_sets, "launches_per_pass": res["n_launch"]},
+        "step_GBps": (fwd_bytes + bwd_bytes) / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": (fwd_bytes + bwd_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"kernel": "sample_fwd_kernel<FP8_E4M3>", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launch_ms": fwd_launch_ms, "bytes_per_launch": fwd_bytes / res["n_launch"],
+                     "bwd": {"kernel": "sample_bwd_kernel", "launch_ms": res["bwd_ms"] / res["n_launch"],
+                             "achieved": bwd_bytes / (res["bwd_ms"] * 1e-3) / 1e9,
+                             "frac": bwd_bytes / (res["bwd_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+        "paper_context": "paper reports 1.40% end-to-end tokens/s overhead (Llama2-134M, A100-40G, Table 1); "
+                         "no params/s or GB/s figure exists for this path",
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            out["roofline"]["traffic"] = json.load(open(traffic_file)).get(args.workload)
+        except Exception:
+            pass
+
+    # ---- cpu_baseline: the oracle, as it stands, on a bounded sample of the same workload ----
+    if not args.no_cpu:
+        import numpy as np
+        import oracle
+        cores = oracle.set_threads(0)
+        descs = res["sets"][0][0]
+        sample = descs[: min(len(descs), 16)]
+        host = [(synth.bits(d.w), d.bt.cpu().numpy(), synth.bits(d.g), d.seed) for d in sample]
+        sp = sum(d.rows * d.cols for d in sample)
+        t0 = time.perf_counter()
+        for (w, bt, g, seed) in host:
+            _, sc = oracle.sample_fwd(w, bt, oracle.FMT_FP8_E4M3, seed, 0)
+            oracle.sample_bwd(g, sc, seed, 0)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sp / dt, "unit": "params/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {len(sample)} tensors of the workload ({sp} params), one fwd+bwd step, "
+                                         f"{dt:.2f} s"}
+    del res
+
+    # ---- extras: other configurations, outside the timed region ----
+    if not args.no_extras:
+        extras = {}
+        torch.cuda.empty_cache()
+        try:
+            other = synth.llama_1b_shapes() if args.workload == "gpt2_124m" else synth.gpt2_124m_shapes()
+            name = "llama_1b" if args.workload == "gpt2_124m" else "gpt2_124m"
+            op = sum(s.rows * s.cols for s in other)
+            r2 = run_workload(other, 10, 2, max(1, min(8, int(1.5e9 // (6 * op)) + 1)))
+            fb = FWD_BYTES_PER_PARAM * op + BLOCK_BYTES * r2["blocks"]
+            bb = BWD_BYTES_PER_PARAM * op + BLOCK_BYTES * r2["blocks"]
+            extras[name] = {"params": op, "params_per_s": op * 10 / r2["wall_s"], "fwd_ms": r2["fwd_ms"],
+                            "bwd_ms": r2["bwd_ms"], "fwd_GBps": fb / r2["fwd_ms"] / 1e6, "bwd_GBps": bb / r2["bwd_ms"] / 1e6,
+                            "step_frac_of_hbm_peak": (fb + bb) / (r2["wall_s"] / 10) / 1e9 / HBM_PEAK_GBS}
+            del r2
+            torch.cuda.empty_cache()
+        except Exception as e:  # pragma: no cover
+            extras["other_workload_error"] = repr(e)
+        try:
+            extras["copy_ceiling"] = copy_ceiling(torch)
+            extras["fused_linear"] = linear_bench(torch, gws, synth, dev)
+        except Exception as e:  # pragma: no cover
+            extras["linear_error"] = repr(e)
+        out["extras"] = extras
+
+    print(json.dumps(out))
+
+
+def _time_ms(torch, fn, iters, warmup=3):
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def copy_ceiling(torch):
+    """A plain device copy of 2 x 1 GiB (torch's copy kernel): what a streaming read+write reaches here."""
+    a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    b = torch.empty_like(a)
+    ms = _time_ms(torch, lambda: b.copy_(a), 10)
+    return {"GBps": 2 * a.numel() / ms / 1e6, "frac_of_hbm_peak": 2 * a.numel() / ms / 1e6 / HBM_PEAK_GBS}
+
+
+def linear_bench(torch, gws, synth, dev):
+    """Fused sampled-weight linear vs unfused (sample kernel + plain GEMM) vs plain BF16 GEMM."""
+    M, K, N = 8192, 2048, 5632
+    x = synth.make_activation(5, M, K, device=dev)
+    t = synth.make_tensor(5, K, N, bt=6.0, device=dev, with_grad=False)
+    w, bt = t["w"], t["bt"]
+    w_hat = torch.empty_like(w)
+    scale = torch.empty(K // 32, N // 32, device=dev)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
+    seed = gws.gws_derive_seed(0, 5)
+    d_full = gws.TensorDesc(rows=K, cols=N, seed=seed, w=w, w_hat=w_hat, bt=bt, scale=scale)
+    pk = gws.pack([d_full])
+    fmt = gws.FMT_FP8_E4M3
+    t_fused = _time_ms(torch, lambda: gws.gws_linear_fwd(x, d_full, y, fmt, 0), 20)
+
+    def unfused():
+        gws.gws_sample_fwd(pk, fmt, 0)
+        gws.gws_gemm_bf16(x, w_hat, y)
+    t_unfused = _time_ms(torch, unfused, 20)
+    t_plain = _time_ms(torch, lambda: gws.gws_gemm_bf16(x, w, y), 20)
+    t_torch = _time_ms(torch, lambda: torch.matmul(x, w, out=y), 20)
+
+    def unfused_torch():
+        gws.gws_sample_fwd(pk, fmt, 0)
+        torch.matmul(x, w_hat, out=y)
+    t_unfused_torch = _time_ms(torch, unfused_torch, 20)
+    t_sample = _time_ms(torch, lambda: gws.gws_sample_fwd(pk, fmt, 0), 20)
+    flop = 2.0 * M * K * N
+    best_plain = min(t_plain, t_torch)
+    return {"shape": [M, K, N], "fused_ms": t_fused, "unfused_ms": t_unfused, "plain_own_ms": t_plain,
+            "plain_torch_ms": t_torch, "unfused_with_torch_gemm_ms": t_unfused_torch, "sample_only_ms": t_sample,
+            "fused_overhead_pct_vs_best_plain": 100.0 * (t_fused - best_plain) / best_plain,
+            "unfused_overhead_pct_vs_best_plain": 100.0 * (min(t_unfused, t_unfused_torch) - best_plain) / best_plain,
+            "fused_overhead_pct_vs_own_plain": 100.0 * (t_fused - t_plain) / t_plain,
+            "fused_TFLOPs": flop / t_fused / 1e9, "plain_own_TFLOPs": flop / t_plain / 1e9,
+            "plain_torch_TFLOPs": flop / t_torch / 1e9,
+            "mfma_frac_of_peak_fused": flop / t_fused / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+
+
+if __name__ == "__main__":
+    main()

@@ -111,6 +111,29 @@ def _stream(stream) -> Optional[int]:
     return int(stream.cuda_stream) or None
 
 
+class PackedTensors:
+    """A descriptor list already marshalled into a C array of ``gws_tensor``.
+
+    The buffers of a training run do not move between steps, so the array can be
+    built once with :func:`pack` and passed to every forward / backward call."""
+
+    def __init__(self, arr, n, keepalive):
+        self.arr, self.n, self._keepalive = arr, n, keepalive
+
+    def __len__(self):
+        return self.n
+
+
+def pack(descs: Sequence[TensorDesc]) -> PackedTensors:
+    return PackedTensors(_marshal(descs), len(descs), list(descs))
+
+
+def _as_c(t):
+    if isinstance(t, PackedTensors):
+        return t.arr, t.n
+    return _marshal(t), len(t)
+
+
 def _marshal(descs: Sequence[TensorDesc]):
     arr = (_CTensor * max(1, len(descs)))()
     for c, d in zip(arr, descs):
@@ -133,13 +156,15 @@ def _check(rc: int, what: str):
 def gws_sample_fwd(t: Sequence[TensorDesc], fmt: int, step: int, stream=None) -> None:
     """Paper Eq. 3 + cast for every descriptor; writes ``w_hat`` and ``scale``."""
     L = load_library()
-    _check(L.gws_sample_fwd(_marshal(t), len(t), int(fmt), int(step), _stream(stream)), "gws_sample_fwd")
+    arr, n = _as_c(t)
+    _check(L.gws_sample_fwd(arr, n, int(fmt), int(step), _stream(stream)), "gws_sample_fwd")
 
 
 def gws_sample_bwd(t: Sequence[TensorDesc], step: int, stream=None) -> None:
     """Paper Eq. 4 for every descriptor; writes ``dbt`` (and ``dw`` unless aliased)."""
     L = load_library()
-    _check(L.gws_sample_bwd(_marshal(t), len(t), int(step), _stream(stream)), "gws_sample_bwd")
+    arr, n = _as_c(t)
+    _check(L.gws_sample_bwd(arr, n, int(step), _stream(stream)), "gws_sample_bwd")
 
 
 def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:

@@ -11,7 +11,7 @@ namespace gws {
 
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup
 constexpr int kTileCols = 256;      // a workgroup covers 32 rows x 256 columns
-constexpr int kMaxTensorsPerLaunch = 40;
+constexpr int kMaxTensorsPerLaunch = 54;
 
 // One tensor as a kernel sees it.  p0..p3 are, for the forward pass,
 // (w, w_hat, bt, scale) and, for the backward pass, (g, dw-or-NULL, dbt, scale).

@@ -1,0 +1,108 @@
+"""GPU parity of gws_linear_fwd (sampling fused into the GEMM's weight operand) and of
+the plain twin gws_gemm_bf16, through the C ABI.
+
+ - w_hat / scale written by the fused kernel: bit-exact against the oracle forward.
+ - Y against the oracle's fp64 GEMM on the oracle's w_hat: |y - ref| <= 2^-8 |ref| +
+   K * 2^-24 * sum|x q| (one BF16 rounding plus fp32 accumulation in any order).
+ - fused Y == plain GEMM on the separately sampled w_hat, bit for bit (same GEMM code).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_11170_amd as gws
+from paper_2505_11170_amd import synth
+from gpu_util import DEV, ensure_built
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def bf16_val(bits):
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def check_y(y_bits, x_bits, q_bits, w_is_nk, rows_sel=None):
+    K = x_bits.shape[1]
+    y64, yabs, _ = oracle.linear_fwd(x_bits, q_bits, w_is_nk=w_is_nk, rows_sel=rows_sel)
+    got = bf16_val(y_bits if rows_sel is None else y_bits[rows_sel])
+    tol = 2.0 ** -8 * np.abs(y64) + K * 2.0 ** -24 * yabs + 1e-30
+    bad = np.abs(got - y64) > tol
+    assert not bad.any(), (np.argwhere(bad)[:5], got[bad][:5], y64[bad][:5])
+
+
+def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, ldx_pad=0, ldy_pad=0):
+    wr, wc = (N, K) if w_is_nk else (K, N)
+    t = synth.make_tensor(200 + seed_id, wr, wc, bt=bt, with_grad=False)
+    x_full = synth.make_activation(300 + seed_id, M, K + ldx_pad)
+    x = x_full.to(DEV)[:, :K]
+    w = t["w"].to(DEV)
+    btd = t["bt"].to(DEV)
+    seed = oracle.derive_seed(0, seed_id)
+    y_store = torch.zeros(M, N + ldy_pad, dtype=torch.bfloat16, device=DEV)
+    y = y_store[:, :N]
+    w_hat = torch.zeros_like(w)
+    nbr, nbc = synth.n_blocks(wr, wc)
+    scale = torch.zeros(nbr, nbc, dtype=torch.float32, device=DEV)
+    desc = gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, w_hat=w_hat, bt=btd, scale=scale)
+    gws.gws_linear_fwd(x, desc, y, fmt, step, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    # 1. sampled weight written by the fused kernel == oracle
+    ref_q, ref_s = oracle.sample_fwd(synth.bits(t["w"]), t["bt"].numpy(), fmt, seed, step)
+    assert (synth.bits(w_hat) == ref_q).all()
+    assert (scale.cpu().numpy().view(np.uint32) == ref_s.view(np.uint32)).all()
+    # 2. Y against the fp64 GEMM
+    x_bits = np.ascontiguousarray(synth.bits(x_full)[:, :K])
+    y_bits = np.ascontiguousarray(synth.bits(y_store)[:, :N])
+    check_y(y_bits, x_bits, ref_q, w_is_nk, rows_sel)
+    if ldy_pad:
+        assert (synth.bits(y_store)[:, N:] == 0).all()          # padding of Y never written
+    # 3. unfused path (sample kernel + plain GEMM) gives the same bits
+    w_hat2 = torch.zeros_like(w)
+    scale2 = torch.zeros_like(scale)
+    gws.gws_sample_fwd([gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, w_hat=w_hat2, bt=btd, scale=scale2)], fmt, step)
+    y2 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(x, w_hat2, y2, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    assert (synth.bits(w_hat2) == ref_q).all()
+    assert (synth.bits(y2) == y_bits).all()
+    # 4. without w_hat / scale outputs the result is the same
+    y3 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_linear_fwd(x, gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, bt=btd), y3, fmt, step, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    assert (synth.bits(y3) == y_bits).all()
+
+
+@pytest.mark.parametrize("w_is_nk", [False, True])
+@pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
+def test_linear_small_shapes(w_is_nk, fmt):
+    run_case(128, 64, 128, w_is_nk, fmt, bt=6.0)
+    run_case(200, 96, 160, w_is_nk, fmt, seed_id=1)                 # ragged M, N not a tile multiple
+    run_case(37, 32, 32, w_is_nk, fmt, seed_id=2, step=3)
+    run_case(300, 256, 416, w_is_nk, fmt, seed_id=3, ldx_pad=8, ldy_pad=16)
+
+
+def test_plain_gemm_vs_fp64():
+    M, K, N = 260, 192, 224
+    x = synth.make_activation(1, M, K)
+    w = synth.make_tensor(1, K, N, with_grad=False)["w"]
+    y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(x.to(DEV), w.to(DEV), y)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y), synth.bits(x), synth.bits(w), False)
+    wt = w.t().contiguous()
+    y2 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(x.to(DEV), wt.to(DEV), y2, w_is_nk=True)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y2), synth.bits(x), synth.bits(wt), True)
+
+
+def test_config5_fused_linear_8192x2048x5632_sampled_rows():
+    M, K, N = 8192, 2048, 5632
+    rows_sel = np.array([0, 1, 31, 127, 128, 4095, 4096, 8000, 8191])
+    run_case(M, K, N, False, gws.FMT_FP8_E4M3, bt=6.0, seed_id=5, rows_sel=rows_sel)
