@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.gwso_nibbles_to_code.restype = ci
         L.gwso_code_to_r.argtypes = [ci]
         L.gwso_code_to_r.restype = ci
+        L.gwso_element_nibble.argtypes = [ci]
+        L.gwso_element_nibble.restype = ci
         L.gwso_noise.argtypes = [i64, i64, i64, i64, u64, u64, vp, vp]
         L.gwso_noise.restype = None
         L.gwso_bf16_rne.argtypes = [ctypes.c_float]
@@ -103,6 +105,10 @@ def nibbles_to_code(n0, n1, n2, n3) -> int:
 
 def code_to_r(code: int) -> int:
     return int(lib().gwso_code_to_r(code))
+
+
+def element_nibble(k: int) -> int:
+    return int(lib().gwso_element_nibble(k))
 
 
 def noise(rows: int, cols: int, seed: int, step: int, row0: int = 0, col0: int = 0):

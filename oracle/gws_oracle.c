@@ -117,10 +117,16 @@ static void group_words(int64_t i, int64_t cg, uint64_t seed, uint64_t step,
   gwso_philox4x32(ctr, key, 10, x);
 }
 
-/* Element k (= j & 7) of a group takes nibble k of each word. */
+/* Which nibble of each Philox word belongs to element k (= j & 7) of a group:
+ * each 32-bit word is seen as two 16-bit halves, the low half serving the even
+ * elements and the high half the odd ones (the way two BF16 values share a
+ * 32-bit register); pair k>>1 takes nibble k>>1 of its half.                 */
+int gwso_element_nibble(int k) { return (k >> 1) + 4 * (k & 1); }
+
 static int element_code(const uint32_t x[4], int k) {
-  return gwso_nibbles_to_code((x[0] >> (4 * k)) & 0xFu, (x[1] >> (4 * k)) & 0xFu,
-                              (x[2] >> (4 * k)) & 0xFu, (x[3] >> (4 * k)) & 0xFu);
+  int sh = 4 * gwso_element_nibble(k);
+  return gwso_nibbles_to_code((x[0] >> sh) & 0xFu, (x[1] >> sh) & 0xFu,
+                              (x[2] >> sh) & 0xFu, (x[3] >> sh) & 0xFu);
 }
 
 /* Noise of a whole [rows x cols] tensor.

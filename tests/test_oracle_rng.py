@@ -99,9 +99,12 @@ def test_noise_uses_counter_col_group_row_step_and_seed_key():
             x = oracle.philox4x32([cg, i, step & 0xFFFFFFFF, step >> 32], [seed & 0xFFFFFFFF, seed >> 32])
             word = 0
             for k in range(8):
-                n = [(xx >> (4 * k)) & 0xF for xx in x]
+                # even elements read the low 16-bit half of each word, odd ones the high half
+                sh = 4 * (k // 2) + 16 * (k % 2)
+                n = [(xx >> sh) & 0xF for xx in x]
                 word |= oracle.nibbles_to_code(*n) << (4 * k)
             assert word == int(packed[i, cg])
+    assert sorted(oracle.element_nibble(k) for k in range(8)) == list(range(8))
 
 
 def test_noise_moments_large_sample():
