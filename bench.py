@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets rotated through (0 = auto)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -79,7 +81,7 @@ def main():
         params = sum(s.rows * s.cols for s in shapes)
         blocks = sum(synth.n_blocks(s.rows, s.cols)[0] * synth.n_blocks(s.rows, s.cols)[1] for s in shapes)
         sets = make_sets(shapes, n_sets, bt=bt)
-        n_launch = (len(shapes) + 53) // 54
+        n_launch = (len(shapes) + 55) // 56
         for s in range(warmup):
             _, p = sets[s % n_sets]
             gws.gws_sample_fwd(p, fmt, s)
@@ -191,6 +193,13 @@ def main():
         except Exception as e:  # pragma: no cover
             extras["linear_error"] = repr(e)
         out["extras"] = extras
+
+    if args.calibrate:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
 
     print(json.dumps(out))
 

@@ -44,7 +44,7 @@ int check_bwd(const gws_tensor& t) {
   return GWS_OK;
 }
 
-void fill_common(TileDesc& d, const gws_tensor& t, uint32_t tile_begin) {
+void fill_common(TileDesc& d, const gws_tensor& t) {
   d.rows = (uint32_t)t.rows;
   d.cols = (uint32_t)t.cols;
   d.ld = (uint32_t)t.ld;
@@ -52,46 +52,57 @@ void fill_common(TileDesc& d, const gws_tensor& t, uint32_t tile_begin) {
   d.cg0 = (uint32_t)(t.col0 / 8);
   d.seed_lo = (uint32_t)t.seed;
   d.seed_hi = (uint32_t)(t.seed >> 32);
-  d.tile_begin = tile_begin;
   d.tiles_x = (uint32_t)((t.cols + kTileCols - 1) / kTileCols);
-  d.pad_ = 0;
 }
 
-inline uint64_t tile_count(const gws_tensor& t) {
-  return (uint64_t)((t.rows + 31) / 32) * (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
+// Workgroups a tensor needs when each walks down `per_wg` block rows of a 256-column strip.
+inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
+  const uint64_t nbr = (uint64_t)((t.rows + 31) / 32);
+  return ((nbr + per_wg - 1) / per_wg) * (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
 }
 
 // Pack descriptors into as few launches as the kernel-argument segment and the
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 int run_batched(const gws_tensor* t, int n, bool fwd, int fmt, uint64_t step, hipStream_t stream) {
+  // Longer walks per workgroup hide more latency but leave fewer workgroups to
+  // balance over the 256 compute units: keep at least ~16 per unit.
+  uint64_t total = 0;
+  for (int i = 0; i < n; ++i)
+    if (t[i].rows > 0 && t[i].cols > 0) total += wg_count(t[i], 1);
+  const uint32_t per_wg = total >= 16384 ? 4u : (total >= 8192 ? 2u : 1u);
+
   LaunchArgs a;
   memset(&a, 0, sizeof a);
   a.step_lo = (uint32_t)step;
   a.step_hi = (uint32_t)(step >> 32);
-  uint64_t tiles = 0;
+  a.tiles_per_wg = per_wg;
+  for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
+  uint64_t wgs = 0;
   auto flush = [&]() -> int {
     if (a.n == 0) return GWS_OK;
-    int rc = fwd ? launch_sample_fwd(a, (uint32_t)tiles, fmt, stream) : launch_sample_bwd(a, (uint32_t)tiles, stream);
+    int rc = fwd ? launch_sample_fwd(a, (uint32_t)wgs, fmt, stream) : launch_sample_bwd(a, (uint32_t)wgs, stream);
     a.n = 0;
-    tiles = 0;
+    wgs = 0;
+    for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
     return rc;
   };
   for (int i = 0; i < n; ++i) {
     if (t[i].rows == 0 || t[i].cols == 0) continue;
-    const uint64_t tc = tile_count(t[i]);
-    if (tc >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
-    if (a.n == (uint32_t)kMaxTensorsPerLaunch || tiles + tc >= 0x7FFFFFFFull) {
+    const uint64_t wc = wg_count(t[i], per_wg);
+    if (wc >= 0x7FFFFFF0ull) return GWS_ERR_SHAPE;
+    if (a.n == (uint32_t)kMaxTensorsPerLaunch || wgs + wc >= 0x7FFFFFF0ull) {
       int rc = flush();
       if (rc != GWS_OK) return rc;
     }
+    a.tile_begin[a.n] = (uint32_t)wgs;
     TileDesc& d = a.t[a.n++];
     if (fwd) {
       d.p0 = t[i].w; d.p1 = t[i].w_hat; d.p2 = (void*)t[i].bt; d.p3 = t[i].scale;
     } else {
       d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
     }
-    fill_common(d, t[i], (uint32_t)tiles);
-    tiles += tc;
+    fill_common(d, t[i]);
+    wgs += wc;
   }
   return flush();
 }

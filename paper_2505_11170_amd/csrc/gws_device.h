@@ -7,10 +7,22 @@
 
 namespace gws {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): the counter-based bit source named in
 // the paper's Sec. 3.4.  One call yields the 128 bits of a group of 8
-// row-contiguous elements (16 bits per element).
+// row-contiguous elements (16 bits per element).  Counter = (column group,
+// row, step lo, step hi), key = per-tensor seed.  Calls of one lane that differ
+// only in the row share the multiplies of the first rounds (the compiler folds
+// them once the calls are inlined side by side).
 // ---------------------------------------------------------------------------
 struct Philox4 {
   uint32_t x0, x1, x2, x3;
@@ -22,8 +34,8 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = n0;
@@ -35,28 +47,51 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 // ---------------------------------------------------------------------------
-// 128 random bits -> eight 4-bit sign-magnitude codes of R (paper Sec. 3.4,
-// Eq. 9 and Eq. 10), evaluated for all eight elements at once: element k owns
-// nibble k of each word.
-//   |R| = 2 : (b|b) & (8 bits all set)                 -> 3/4 * 2^-8
-//   |R| = 1 : (b|b) & (b|b) & b, unless |R| = 2        -> (3/4)^2 * 2^-1 * (1 - P(|R|=2))
-//   sign    : 1 bit
-// code = sign<<3 | |R|, element k in bits 4k..4k+3.
+// 128 random bits -> the noise of eight elements (paper Sec. 3.4, Eq. 9 and
+// Eq. 10), evaluated for all eight at once on nibble planes.  Each element owns
+// one nibble position in each of the four words (16 independent bits):
+//   |R| = 2 : (b|b) & (8 bits all set)              -> 3/4 * 2^-8
+//   |R| = 1 : (b|b) & (b|b) & b, unless |R| = 2     -> (3/4)^2 * 2^-1 * (1 - P(|R|=2))
+//   sign    : 1 bit (bit 3 of the x3 nibble; x3 is kept as is)
+// Element k of a group owns nibble (k>>1) + 4*(k&1): the two BF16 values of a
+// 32-bit register take their bits from the low and the high half of each word.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t noise_codes(const Philox4& x) {
-  uint32_t all8 = x.x0 & x.x1;      // per nibble: AND of the 8 bits, folded below
+struct Noise {
+  uint32_t nz;  // bit 0 of each nibble: R != 0
+  uint32_t m2;  // bit 0 of each nibble: |R| == 2
+  uint32_t x3;  // bit 3 of each nibble: sign
+};
+
+__device__ __forceinline__ Noise noise_planes(const Philox4& x) {
+  uint32_t all8 = x.x0 & x.x1;
   all8 &= all8 >> 1;
-  all8 &= all8 >> 2;                // bit 0 of each nibble = all 8 bits set
+  all8 &= all8 >> 2;                      // bit 0 of each nibble: all 8 bits set
   const uint32_t v = x.x2 | (x.x2 >> 1);  // bit 0: b|b (A), bit 2: b|b (C)
   const uint32_t y = x.x3 | (x.x3 >> 1);  // bit 0: b|b (D)
-  const uint32_t m2 = all8 & v & 0x11111111u;
-  const uint32_t m1 = (v >> 2) & y & (x.x3 >> 2) & ~m2 & 0x11111111u;
-  return (x.x3 & 0x88888888u) | (m2 << 1) | m1;
+  Noise n;
+  n.m2 = all8 & v & 0x11111111u;
+  // (C & D & E) | m2: where m2 is set the element is |R| = 2, elsewhere |R| = 1
+  n.nz = ((v >> 2) & y & (x.x3 >> 2) & 0x11111111u) | n.m2;
+  n.x3 = x.x3;
+  return n;
 }
 
-__device__ __forceinline__ uint32_t group_codes(uint32_t cg, uint32_t row, uint32_t step_lo,
-                                                uint32_t step_hi, uint32_t seed_lo, uint32_t seed_hi) {
-  return noise_codes(philox4x32_10(cg, row, step_lo, step_hi, seed_lo, seed_hi));
+__device__ __forceinline__ Noise group_noise(uint32_t cg, uint32_t row, uint32_t step_lo, uint32_t step_hi,
+                                             uint32_t seed_lo, uint32_t seed_hi) {
+  return noise_planes(philox4x32_10(cg, row, step_lo, step_hi, seed_lo, seed_hi));
+}
+
+// Nibble position of element k of a group.
+__host__ __device__ constexpr int element_nibble(int k) { return (k >> 1) + 4 * (k & 1); }
+
+// The packed output format of Sec. 3.4: 4-bit sign-magnitude codes, element k
+// in bits 4k..4k+3 (only the noise dump needs it).
+__device__ __forceinline__ uint32_t packed_codes(const Noise& n) {
+  const uint32_t c = (n.x3 & 0x88888888u) | (n.nz + n.m2);  // per nibble: sign<<3 | |R|
+  uint32_t out = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) out |= ((c >> (4 * element_nibble(k))) & 0xFu) << (4 * k);
+  return out;
 }
 
 // ---------------------------------------------------------------------------
@@ -84,14 +119,26 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
   return u >> 16;
 }
 
+// Two fp32 -> packed BF16 pair (lo in bits 0..15), round to nearest even, in
+// hardware (v_cvt_pk_bf16_f32; identical to the integer rounding above for
+// every finite input).
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+  bf16x2 p = {(__bf16)lo, (__bf16)hi};
+  uint32_t u;
+  __builtin_memcpy(&u, &p, 4);
+  return u;
+}
+
 // ---------------------------------------------------------------------------
 // Per-block constants of the forward pass.
 // ---------------------------------------------------------------------------
 struct BlockScale {
   float s32;        // max|w| * 2^(1-b_t), unrounded fp32 (stored; Eq. 4 reuses it)
-  float s;          // bf16_rne(s32) as fp32: the step of the PQN
+  uint32_t s_bits;  // bf16_rne(s32) as fp32 bits (sign clear): the step of the PQN
+  float x_scale;    // cast: X = 2^(Ea + 1 - EMAX) as fp32
   uint32_t emin_b;  // cast: fp32 exponent field (<<23) of the lowest normal binade of X*format
   uint32_t max_b;   // cast: fp32 bits of max*X (saturation bound)
+  bool hw_safe;     // cast: no element of the block can exceed max*X (a + 2s <= max*X)
 };
 
 template <int EMAX, int EMIN>
@@ -101,8 +148,11 @@ __device__ __forceinline__ void cast_constants(uint32_t a16, BlockScale& b) {
   // supported domain and only have to stay in bounds).
   int ef = (int)(a16 >> 7);
   ef = ef < 27 ? 27 : ef;
-  b.emin_b = (uint32_t)(ef + 1 - EMAX + EMIN) << 23;  // X = 2^(Ea+1-EMAX), lowest normal = X * 2^EMIN
+  b.x_scale = __uint_as_float((uint32_t)(ef + 1 - EMAX) << 23);
+  b.emin_b = (uint32_t)(ef + 1 - EMAX + EMIN) << 23;  // lowest normal = X * 2^EMIN
   b.max_b = ((uint32_t)(ef + 1) << 23) | 0x00600000u; // 1.75 * 2^EMAX * X = 1.75 * 2^(Ea+1)
+  const float a = __uint_as_float(a16 << 16);
+  b.hw_safe = a + 2.0f * __uint_as_float(b.s_bits) <= __uint_as_float(b.max_b);
 }
 
 __device__ __forceinline__ BlockScale block_scale(uint32_t a16, float bt) {
@@ -110,64 +160,160 @@ __device__ __forceinline__ BlockScale block_scale(uint32_t a16, float bt) {
   const float a = __uint_as_float(a16 << 16);
   const float p = exp2_fixed(1.0f - bt);
   b.s32 = a * p;
-  b.s = __uint_as_float(bf16_rne_bits(b.s32) << 16);
+  b.s_bits = bf16_rne_bits(b.s32) << 16;
+  b.x_scale = 1.0f;
   b.emin_b = 0;
   b.max_b = 0;
+  b.hw_safe = true;
   return b;
 }
 
 // ---------------------------------------------------------------------------
-// Block-scaled fp_{e,m} cast (paper Sec. 3.3) of a BF16 value held in fp32:
-// round to nearest even onto the grid of spacing 2^(max(e_v, emin) - M), by
-// adding and subtracting 2^(23 - M) times that binade (the fp32 adder performs
-// the rounding), then saturate and restore the sign.
+// Block-scaled fp_{e,m} cast (paper Sec. 3.3) of a BF16 value held in fp32, in
+// plain arithmetic: round to nearest even onto the grid of spacing
+// 2^(max(e_v, emin) - M) by adding and subtracting 2^(23 - M) times that binade
+// (the fp32 adder performs the rounding), then saturate and restore the sign.
 // ---------------------------------------------------------------------------
 template <int M>
-__device__ __forceinline__ float cast_scaled(float v, const BlockScale& b) {
-  const uint32_t u = __float_as_uint(v);
+__device__ __forceinline__ uint32_t cast_scaled_bits(uint32_t h16, const BlockScale& b) {
+  const uint32_t u = h16 << 16;
   const uint32_t au = u & 0x7FFFFFFFu;
   uint32_t eb = au & 0x7F800000u;
   eb = eb > b.emin_b ? eb : b.emin_b;
   const float c = __uint_as_float(eb + ((uint32_t)(23 - M) << 23));
   float r = (__uint_as_float(au) + c) - c;
   r = fminf(r, __uint_as_float(b.max_b));
-  return __uint_as_float(__float_as_uint(r) | (u & 0x80000000u));
+  return (__float_as_uint(r) | (u & 0x80000000u)) >> 16;
 }
 
-// One element of Eq. 3 + cast: w (BF16 value in fp32), its 4-bit noise code and
-// the block constants -> BF16 bits of w_hat.
+// Cast of a packed BF16 pair.  FP8-E4M3 goes through the hardware converters
+// (v_cvt_scalef32_pk_fp8_bf16 and back: round to nearest even, gradual
+// underflow, division by the power-of-two scale), which produce NaN instead of
+// saturating, so they are used only where the block cannot overflow.
 template <int FMT>
-__device__ __forceinline__ uint32_t sample_element(float w, uint32_t code, const BlockScale& b) {
-  // PQN = R * s in sign-magnitude: |R| * s is exact, the sign bit is placed as is
-  const float mag = (float)(code & 3u);
-  const float pqn = __uint_as_float(__float_as_uint(mag * b.s) | ((code & 8u) << 28));
-  const float sum = w + pqn;  // fp32 add, then one RNE to BF16 == exact BF16 add
-  const uint32_t h = bf16_rne_bits(sum);
-  if (FMT == 0) return h;
-  const float v = __uint_as_float(h << 16);
-  const float q = (FMT == 1) ? cast_scaled<3>(v, b) : cast_scaled<2>(v, b);
-  return __float_as_uint(q) >> 16;
+__device__ __forceinline__ uint32_t cast_pair(uint32_t pk, const BlockScale& b, bool hw, i16x2& chain) {
+  if (FMT == 0) return pk;
+  if (FMT == 1 && hw) {
+    bf16x2 v;
+    __builtin_memcpy(&v, &pk, 4);
+    // the converter writes one 16-bit half of its destination and keeps the other:
+    // chaining the previous result as "old" avoids a register clear per call
+    chain = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(chain, v, b.x_scale, false);
+    uint32_t cu;
+    __builtin_memcpy(&cu, &chain, 4);
+    const bf16x2 r = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(cu, b.x_scale, false);
+    uint32_t ru;
+    __builtin_memcpy(&ru, &r, 4);
+    return ru;
+  }
+  constexpr int M = (FMT == 1) ? 3 : 2;
+  return cast_scaled_bits<M>(pk & 0xFFFFu, b) | (cast_scaled_bits<M>(pk >> 16, b) << 16);
 }
 
-// Max / sum over the 32 lanes of a wavefront that share a 32x32 block.  Lane =
-// 8 * row_in_8 + column_group; a block owns column groups {0..3} or {4..7}, so
-// the lanes of one block differ in lane bits 0, 1, 3, 4, 5.
+// Byte i of x as fp32 (v_cvt_f32_ubyte<i>).  The empty asm hides what is known
+// about the other bits of x, so the byte extraction is not rewritten into a
+// shift-and-mask pair.
+__device__ __forceinline__ uint32_t opaque(uint32_t x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+template <int I>
+__device__ __forceinline__ float byte_to_f32(uint32_t x) {
+  return (float)((x >> (8 * I)) & 0xFFu);
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 3 + cast on one 16-byte group (8 BF16 in 4 registers).  PQN = R * s is
+// formed in sign-magnitude: |R| * s is exact and the sign bit is placed as is
+// (R = -0 gives -0.0); the fp32 fused multiply-add followed by one RNE to BF16
+// equals the exact BF16 sum.
+// ---------------------------------------------------------------------------
+template <int FMT>
+__device__ __forceinline__ u32x4 sample_group(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
+  const uint32_t mag = n.nz + n.m2;  // per nibble: |R| in {0, 1, 2}
+  const uint32_t me = opaque(mag & 0x0F0F0F0Fu);         // byte i: |R| of nibble 2i
+  const uint32_t mo = opaque((mag >> 4) & 0x0F0F0F0Fu);  // byte i: |R| of nibble 2i+1
+  // element 2d sits in nibble d, element 2d+1 in nibble d+4
+  const float m[8] = {byte_to_f32<0>(me), byte_to_f32<2>(me), byte_to_f32<0>(mo), byte_to_f32<2>(mo),
+                      byte_to_f32<1>(me), byte_to_f32<3>(me), byte_to_f32<1>(mo), byte_to_f32<3>(mo)};
+  i16x2 chain = {0, 0};
+  u32x4 out;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const int n_lo = d, n_hi = d + 4;
+    // s with the sign bit of the nibble: (x3 << sh) & 0x80000000 | s, one shift and one bit-op
+    const uint32_t sh_lo = n.x3 << (28 - 4 * n_lo);
+    const uint32_t sh_hi = (n_hi == 7) ? n.x3 : (n.x3 << (28 - 4 * n_hi));
+    const float s_lo = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_lo, 0x80000000u, b.s_bits, 0xEA));
+    const float s_hi = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_hi, 0x80000000u, b.s_bits, 0xEA));
+    const float w_lo = __uint_as_float(w[d] << 16), w_hi = __uint_as_float(w[d] & 0xFFFF0000u);
+    const float sum_lo = __fmaf_rn(m[2 * d], s_lo, w_lo);
+    const float sum_hi = __fmaf_rn(m[2 * d + 1], s_hi, w_hi);
+    out[d] = cast_pair<FMT>(pack_bf16_rne(sum_lo, sum_hi), b, hw, chain);
+  }
+  return out;
+}
+
+// sum over one group of g .* (2R), two elements per v_dot2 (products exact, fp32
+// accumulation).  2R in {0, +-2, +-4} has the BF16 patterns sign<<15 | nz<<14 |
+// m2<<7, three single-bit deposits per element.
+__device__ __forceinline__ float dot_group_2r(const u32x4 g, const Noise& n, float acc) {
+  const uint32_t u = (n.x3 & 0x88888888u) | (n.nz << 2);  // per nibble: bit 3 sign, bit 2 nz
+  const uint32_t v = n.m2 << 3;                            // per nibble: bit 3 m2
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t hi2 = (u << (12 - 4 * d)) & 0xC000C000u;
+    const uint32_t m2b = (d <= 1 ? (v << (4 - 4 * d)) : (v >> (4 * d - 4))) & 0x00800080u;
+    const uint32_t pat = hi2 | m2b;
+    const uint32_t gd = g[d];
+    bf16x2 gv, rv;
+    __builtin_memcpy(&gv, &gd, 4);
+    __builtin_memcpy(&rv, &pat, 4);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(gv, rv, acc, false);
+  }
+  return acc;
+}
+
+// ---------------------------------------------------------------------------
+// Cross-lane reductions over the 32 lanes of a wavefront that share a 32x32
+// block.  Lane = 8 * row_in_8 + column_group; a block owns column groups
+// {0..3} or {4..7}, so its lanes differ in lane bits 0, 1, 3, 4, 5.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
 __device__ __forceinline__ uint32_t block_max_u32(uint32_t v) {
-  v = max(v, (uint32_t)__shfl_xor((int)v, 1));
-  v = max(v, (uint32_t)__shfl_xor((int)v, 2));
-  v = max(v, (uint32_t)__shfl_xor((int)v, 8));
-  v = max(v, (uint32_t)__shfl_xor((int)v, 16));
+  v = max(v, dpp_u32<0xB1>(v));   // quad_perm [1,0,3,2]: lane ^ 1
+  v = max(v, dpp_u32<0x4E>(v));   // quad_perm [2,3,0,1]: lane ^ 2
+  v = max(v, dpp_u32<0x128>(v));  // row_ror 8: lane ^ 8 within a row of 16
+  v = max(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));  // lane ^ 16
   v = max(v, (uint32_t)__shfl_xor((int)v, 32));
   return v;
 }
 
 __device__ __forceinline__ float block_sum_f32(float v) {
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 8);
-  v += __shfl_xor(v, 16);
+  v += __uint_as_float(dpp_u32<0xB1>(__float_as_uint(v)));
+  v += __uint_as_float(dpp_u32<0x4E>(__float_as_uint(v)));
+  v += __uint_as_float(dpp_u32<0x128>(__float_as_uint(v)));
+  v += __uint_as_float((uint32_t)__builtin_amdgcn_ds_swizzle((int)__float_as_uint(v), 0x401F));
   v += __shfl_xor(v, 32);
   return v;
+}
+
+// max|w| of a 16-byte group, as BF16 magnitude bits in both halves of a register.
+__device__ __forceinline__ uint32_t absmax_pk(const u32x4 w, uint32_t m) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t a = w[d] & 0x7FFF7FFFu;
+    u16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &m, 4);
+    const u16x2 z = __builtin_elementwise_max(x, y);
+    __builtin_memcpy(&m, &z, 4);
+  }
+  return m;
 }
 
 }  // namespace gws

@@ -11,7 +11,7 @@ namespace gws {
 
 constexpr int kThreads = 256;       // 4 wavefronts per workgroup
 constexpr int kTileCols = 256;      // a workgroup covers 32 rows x 256 columns
-constexpr int kMaxTensorsPerLaunch = 54;
+constexpr int kMaxTensorsPerLaunch = 56;
 
 // One tensor as a kernel sees it.  p0..p3 are, for the forward pass,
 // (w, w_hat, bt, scale) and, for the backward pass, (g, dw-or-NULL, dbt, scale).
@@ -23,22 +23,24 @@ struct TileDesc {
   uint32_t rows, cols, ld;
   uint32_t row0, cg0;          // shard origin: row offset, column-group (col0 / 8) offset
   uint32_t seed_lo, seed_hi;
-  uint32_t tile_begin;         // first workgroup of this tensor within the launch
   uint32_t tiles_x;            // workgroup tiles per block row = ceil(cols / 256)
-  uint32_t pad_;
 };
 
 // Passed by value: lives in the kernel-argument segment (at most 4 KiB).
 struct LaunchArgs {
+  // First workgroup of every tensor within the launch; entries past n hold 0x7FFFFFFF.
+  // Kept apart from the descriptors so a wavefront reads the whole prefix with a few
+  // wide scalar loads instead of one dependent load per tensor.
+  uint32_t tile_begin[kMaxTensorsPerLaunch];
   TileDesc t[kMaxTensorsPerLaunch];
   uint32_t n;
   uint32_t step_lo, step_hi;
-  uint32_t pad_;
+  uint32_t tiles_per_wg;       // consecutive block rows one workgroup walks down (>= 1)
 };
 static_assert(sizeof(LaunchArgs) <= 3968, "kernel arguments must fit the 4 KiB segment");
 
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_tiles, int fmt, hipStream_t stream);
-int launch_sample_bwd(const LaunchArgs& a, uint32_t n_tiles, hipStream_t stream);
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, hipStream_t stream);
+int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_noise_packed(uint32_t* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0,
                         uint64_t seed, uint64_t step, hipStream_t stream);
 

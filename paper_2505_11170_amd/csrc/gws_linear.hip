@@ -70,14 +70,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g) {
   }
   const uint32_t nbc = W_NK ? (g.K >> 5) : (g.N >> 5);  // blocks per storage row of b_t / scale
 
-  uint4 ra[2], rb[2];
+  u32x4 ra[2], rb[2];
   auto load_tiles = [&](uint32_t kt) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      ra[i] = *(const uint4*)(a_ptr[i] + (size_t)kt * BK);
-      if (W_NK) rb[i] = *(const uint4*)(b_ptr[i] + (size_t)kt * BK);
-      else rb[i] = *(const uint4*)(b_ptr[i] + (size_t)kt * BK * g.ldw);
-      if (!blk_ok) rb[i] = make_uint4(0, 0, 0, 0);
+      ra[i] = *(const u32x4*)(a_ptr[i] + (size_t)kt * BK);
+      if (W_NK) rb[i] = *(const u32x4*)(b_ptr[i] + (size_t)kt * BK);
+      else rb[i] = *(const u32x4*)(b_ptr[i] + (size_t)kt * BK * g.ldw);
+      if (!blk_ok) rb[i] = u32x4{0, 0, 0, 0};
     }
   };
 
@@ -85,14 +85,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g) {
   auto sample_block = [&](uint32_t kt) {
     uint32_t m = 0;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const uint32_t e[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        m = max(m, e[k] & 0x7FFFu);
-        m = max(m, (e[k] >> 16) & 0x7FFFu);
-      }
-    }
+    for (int i = 0; i < 2; ++i) m = absmax_pk(rb[i], m);
+    m = max(m & 0xFFFFu, m >> 16);
     const uint32_t a16 = wave_max_u32(m);
     // storage coordinates of the block: (block row, block col) in the stored matrix
     const uint32_t brow = W_NK ? (blk_n >> 5) : kt;
@@ -103,35 +97,27 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs g) {
     if (FMT == 2) cast_constants<4, -2>(a16, b);
     const bool writer = blk_ok && tile_m == 0 && g.w_hat != nullptr;
     if (writer && lane == 0) g.scale[(size_t)brow * nbc + bcol] = b.s32;
+    const bool hw = (FMT == 1) && b.hw_safe;  // uniform: the whole wavefront holds one block
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const uint32_t srow = (W_NK ? blk_n : kt * 32) + b_r + 16 * i;        // storage row
       const uint32_t scol = (W_NK ? kt * 32 : blk_n) + b_q * 8;             // storage column
-      const uint32_t codes = group_codes(g.cg0 + (scol >> 3), g.row0 + srow, g.step_lo, g.step_hi,
-                                         g.seed_lo, g.seed_hi);
-      const uint32_t e[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
-      uint32_t o[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const uint32_t lo = sample_element<FMT>(__uint_as_float(e[k] << 16), (codes >> (8 * k)) & 0xFu, b);
-        const uint32_t hi =
-            sample_element<FMT>(__uint_as_float(e[k] & 0xFFFF0000u), (codes >> (8 * k + 4)) & 0xFu, b);
-        o[k] = lo | (hi << 16);
-      }
-      rb[i] = make_uint4(o[0], o[1], o[2], o[3]);
-      if (writer) *(uint4*)(g.w_hat + (size_t)srow * g.ldw + scol) = rb[i];
+      const Noise n = group_noise(g.cg0 + (scol >> 3), g.row0 + srow, g.step_lo, g.step_hi,
+                                  g.seed_lo, g.seed_hi);
+      rb[i] = hw ? sample_group<FMT>(rb[i], n, b, true) : sample_group<FMT>(rb[i], n, b, false);
+      if (writer) *(u32x4*)(g.w_hat + (size_t)srow * g.ldw + scol) = rb[i];
     }
   };
 
   auto store_lds = [&]() {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      *(uint4*)(As + a_row[i] * LDSP + a_kg * 8) = ra[i];
+      *(u32x4*)(As + a_row[i] * LDSP + a_kg * 8) = ra[i];
       if (W_NK) {
-        *(uint4*)(Bs + (32 * wave + b_r + 16 * i) * LDSP + b_q * 8) = rb[i];
+        *(u32x4*)(Bs + (32 * wave + b_r + 16 * i) * LDSP + b_q * 8) = rb[i];
       } else {
         // transpose while storing: the lane holds 8 consecutive n at one k
-        const uint32_t e[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
+        const uint32_t e[4] = {rb[i][0], rb[i][1], rb[i][2], rb[i][3]};
         const uint32_t k = b_r + 16 * i, nb = 32 * wave + b_q * 8;
 #pragma unroll
         for (int j = 0; j < 8; ++j)

@@ -7,6 +7,9 @@
 // therefore covers 8 rows x 128 contiguous bytes, the four waves of a workgroup
 // sit side by side (512 contiguous bytes per row), and the per-block reductions
 // (absmax, sum of g.*R) stay inside one wavefront: no LDS, no barrier.
+// A workgroup walks down `tiles_per_wg` consecutive block rows of its 256-column
+// strip and issues the loads of the next tile before it computes the current
+// one, so a wavefront hides most of its own memory latency.
 // One Philox4x32-10 call yields the 16 bits x 8 elements of one 16-byte group,
 // so the noise lives only in registers (2 bytes per parameter of HBM traffic per
 // operand, Sec. 3.5; the 0.5 byte per parameter temporary of the paper is gone).
@@ -26,167 +29,219 @@ __device__ __forceinline__ int valid_count(uint32_t row, uint32_t col, uint32_t 
   return left >= 8 ? 8 : (int)left;
 }
 
-__device__ __forceinline__ void locate(const LaunchArgs& a, int& ti, uint32_t& by, uint32_t& bx) {
+// Which tensor, which block-row group and which column strip this workgroup owns.
+// Pure scalar arithmetic: tile_begin[] ascends, unused entries are 0x7FFFFFFF, so
+// (wg - tile_begin[i]) has its top bit clear exactly for the tensors that start
+// at or before wg.
+__device__ __forceinline__ void locate(const LaunchArgs& a, int& ti, uint32_t& byg, uint32_t& bx) {
   const uint32_t wg = blockIdx.x;
-  ti = 0;
-  for (int i = 1; i < (int)a.n; ++i)
-    if (a.t[i].tile_begin <= wg) ti = i;
-  const uint32_t local = wg - a.t[ti].tile_begin;
-  by = local / a.t[ti].tiles_x;
-  bx = local - by * a.t[ti].tiles_x;
+  uint32_t after = 0;
+#pragma unroll
+  for (int i = 0; i < kMaxTensorsPerLaunch; ++i) after += (wg - a.tile_begin[i]) >> 31;
+  ti = kMaxTensorsPerLaunch - 1 - (int)after;
+  const uint32_t local = wg - a.tile_begin[ti];
+  byg = local / a.t[ti].tiles_x;
+  bx = local - byg * a.t[ti].tiles_x;
 }
 
-template <int FMT>
-__global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
-  int ti;
-  uint32_t by, bx;
-  locate(a, ti, by, bx);
-  const TileDesc& d = a.t[ti];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint32_t col_base = bx * kTileCols + wave * 64;
-  if (col_base >= d.cols) return;  // whole wavefront past the right edge
+__device__ __forceinline__ u32x4 load16(const uint16_t* p) {
+  return __builtin_nontemporal_load((const u32x4*)p);
+}
+__device__ __forceinline__ void store16(uint16_t* p, const u32x4 v) {
+  __builtin_nontemporal_store(v, (u32x4*)p);
+}
+
+// Zero the elements of a group that lie past the right edge (nv valid of 8).
+__device__ __forceinline__ u32x4 mask_group(u32x4 v, int nv) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k >= nv) v[k >> 1] &= (k & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+  return v;
+}
+
+__device__ __forceinline__ void store_partial(uint16_t* dst, const u32x4 v, int nv) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k < nv) dst[k] = (uint16_t)(v[k >> 1] >> ((k & 1) * 16));
+}
+
+// The four 16-byte groups a lane holds of one wavefront tile.
+struct Tile {
+  u32x4 v[4];
+  int nv[4];   // valid elements per group (8 everywhere on a full tile)
+  bool full;   // the 32x64 tile lies inside the tensor: no validity tests needed
+};
+
+// A 16-byte load never leaves its row: ld % 8 == 0 and ld >= cols.
+__device__ __forceinline__ Tile load_tile(const uint16_t* __restrict__ src, const TileDesc& d, uint32_t by,
+                                          uint32_t col_base, uint32_t col, uint32_t r0) {
+  Tile t;
+  const uint32_t row_base = by * 32;
+  t.full = (row_base + 32 <= d.rows) && (col_base + 64 <= d.cols);
+  if (t.full) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      t.nv[i] = 8;
+      t.v[i] = load16(src + (size_t)(row_base + r0 + 8 * i) * d.ld + col);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t row = row_base + r0 + 8 * i;
+      t.nv[i] = valid_count(row, col, d.rows, d.cols);
+      t.v[i] = u32x4{0, 0, 0, 0};
+      if (t.nv[i] > 0) t.v[i] = load16(src + (size_t)row * d.ld + col);
+    }
+  }
+  return t;
+}
+
+template <int FMT, bool FULL>
+__device__ __forceinline__ void fwd_tile(const LaunchArgs& a, const TileDesc& d, Tile& t, uint32_t by,
+                                         uint32_t col_base, uint32_t lane) {
   const uint32_t row_base = by * 32;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   const uint32_t col = col_base + gc * 8;
-  const uint16_t* __restrict__ w = (const uint16_t*)d.p0;
   uint16_t* __restrict__ w_hat = (uint16_t*)d.p1;
   const float* __restrict__ bt = (const float*)d.p2;
   float* __restrict__ scale = (float*)d.p3;
-  const bool full = (row_base + 32 <= d.rows) && (col_base + 64 <= d.cols);
 
-  // ---- load the tile (a 16-byte load never leaves its row: ld % 8 == 0) ----
-  uint4 v[4];
-  int nv[4];
+  if (!FULL) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t row = row_base + r0 + 8 * i;
-    nv[i] = full ? 8 : valid_count(row, col, d.rows, d.cols);
-    v[i] = make_uint4(0, 0, 0, 0);
-    if (nv[i] > 0) v[i] = *(const uint4*)(w + (size_t)row * d.ld + col);
-    if (nv[i] > 0 && nv[i] < 8) {  // ragged right edge: elements past cols do not exist
-      uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (k >= nv[i]) e[k >> 1] &= (k & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-      v[i] = make_uint4(e[0], e[1], e[2], e[3]);
-    }
+    for (int i = 0; i < 4; ++i)
+      if (t.nv[i] < 8) t.v[i] = mask_group(t.v[i], t.nv[i]);  // elements past cols do not exist
   }
 
   // ---- a = max_{b_l}|w| on the magnitude bits (exact) ----
   uint32_t m = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      m = max(m, e[k] & 0x7FFFu);
-      m = max(m, (e[k] >> 16) & 0x7FFFu);
-    }
-  }
+  for (int i = 0; i < 4; ++i) m = absmax_pk(t.v[i], m);
+  m = max(m & 0xFFFFu, m >> 16);
   const uint32_t a16 = block_max_u32(m);
 
   // ---- per-block scale ----
   const uint32_t nbc = (d.cols + 31) >> 5;
   const uint32_t bcol = (col_base >> 5) + (gc >> 2);
-  const bool block_exists = bcol < nbc;
+  const bool block_exists = FULL || bcol < nbc;
   const float btv = block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f;
   BlockScale b = block_scale(a16, btv);
   if (FMT == 1) cast_constants<8, -6>(a16, b);
   if (FMT == 2) cast_constants<4, -2>(a16, b);
   if (block_exists && (gc & 3) == 0 && r0 == 0) scale[(size_t)by * nbc + bcol] = b.s32;
+  // hardware FP8 converters only if neither block of this wavefront can overflow
+  const bool hw = (FMT == 1) && (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0);
 
   // ---- noise, add, round, cast, store ----
   const uint32_t cg = d.cg0 + (col >> 3);
+  auto finish = [&](bool use_hw) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (!FULL && t.nv[i] == 0) continue;
+      const uint32_t row = row_base + r0 + 8 * i;
+      const Noise n = group_noise(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
+      const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
+      uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+      if (FULL || t.nv[i] == 8) store16(dst, o);
+      else store_partial(dst, o, t.nv[i]);
+    }
+  };
+  if (FMT == 1 && hw) finish(true);
+  else finish(false);
+}
+
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
+  int ti;
+  uint32_t byg, bx;
+  locate(a, ti, byg, bx);
+  const TileDesc& d = a.t[ti];
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t col_base = bx * kTileCols + wave * 64;
+  if (col_base >= d.cols) return;  // whole wavefront past the right edge
+  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
+  const uint16_t* __restrict__ w = (const uint16_t*)d.p0;
+  const uint32_t nbr = (d.rows + 31) >> 5;
+  const uint32_t by0 = byg * a.tiles_per_wg;
+  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
+
+  Tile cur = load_tile(w, d, by0, col_base, col, r0);
+  for (uint32_t by = by0; by < by_end; ++by) {
+    Tile nxt;
+    const bool more = by + 1 < by_end;
+    if (more) nxt = load_tile(w, d, by + 1, col_base, col, r0);  // in flight during the compute below
+    if (cur.full) fwd_tile<FMT, true>(a, d, cur, by, col_base, lane);
+    else fwd_tile<FMT, false>(a, d, cur, by, col_base, lane);
+    if (more) cur = nxt;
+  }
+}
+
+template <bool FULL, bool COPY>
+__device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d, const Tile& t, uint32_t by,
+                                         uint32_t col_base, uint32_t lane) {
+  const uint32_t row_base = by * 32;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const uint32_t col = col_base + gc * 8;
+  uint16_t* __restrict__ dw = (uint16_t*)d.p1;
+  float* __restrict__ dbt = (float*)d.p2;
+  const float* __restrict__ scale = (const float*)d.p3;
+  const uint32_t cg = d.cg0 + (col >> 3);
+
+  // sum_{b_l}(g .* R), accumulated as sum(g .* 2R) / 2: every product is exact
+  // in fp32, the order of the additions is fixed (per lane group by group, two
+  // elements per step, then the lane tree), so the result is reproducible.
+  float acc = 0.0f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (nv[i] == 0) continue;
+    if (!FULL && t.nv[i] == 0) continue;
     const uint32_t row = row_base + r0 + 8 * i;
-    const uint32_t codes = group_codes(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
-    const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-    uint32_t o[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t lo = sample_element<FMT>(__uint_as_float(e[k] << 16), (codes >> (8 * k)) & 0xFu, b);
-      const uint32_t hi =
-          sample_element<FMT>(__uint_as_float(e[k] & 0xFFFF0000u), (codes >> (8 * k + 4)) & 0xFu, b);
-      o[k] = lo | (hi << 16);
+    if (COPY) {  // dL/dw = dL/dw_hat, bit for bit
+      uint16_t* dst = dw + (size_t)row * d.ld + col;
+      if (FULL || t.nv[i] == 8) store16(dst, t.v[i]);
+      else store_partial(dst, t.v[i], t.nv[i]);
     }
-    uint16_t* dst = w_hat + (size_t)row * d.ld + col;
-    if (nv[i] == 8) {
-      *(uint4*)dst = make_uint4(o[0], o[1], o[2], o[3]);
-    } else {
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (k < nv[i]) dst[k] = (uint16_t)(o[k >> 1] >> ((k & 1) * 16));
-    }
+    const Noise n = group_noise(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
+    const u32x4 gv = (FULL || t.nv[i] == 8) ? t.v[i] : mask_group(t.v[i], t.nv[i]);
+    acc = dot_group_2r(gv, n, acc);
+  }
+  acc = block_sum_f32(acc) * 0.5f;
+
+  const uint32_t nbc = (d.cols + 31) >> 5;
+  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
+  if ((FULL || bcol < nbc) && (gc & 3) == 0 && r0 == 0) {
+    const float s32 = scale[(size_t)by * nbc + bcol];
+    const float neg_ln2 = __uint_as_float(0xBF317218u);  // -ln 2
+    dbt[(size_t)by * nbc + bcol] = (neg_ln2 * s32) * acc;
   }
 }
 
 __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a) {
   int ti;
-  uint32_t by, bx;
-  locate(a, ti, by, bx);
+  uint32_t byg, bx;
+  locate(a, ti, byg, bx);
   const TileDesc& d = a.t[ti];
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint32_t col_base = bx * kTileCols + wave * 64;
   if (col_base >= d.cols) return;
-  const uint32_t row_base = by * 32;
-  const uint32_t gc = lane & 7, r0 = lane >> 3;
-  const uint32_t col = col_base + gc * 8;
+  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
   const uint16_t* __restrict__ g = (const uint16_t*)d.p0;
-  uint16_t* __restrict__ dw = (uint16_t*)d.p1;  // NULL: pass-through is an alias
-  float* __restrict__ dbt = (float*)d.p2;
-  const float* __restrict__ scale = (const float*)d.p3;
-  const bool full = (row_base + 32 <= d.rows) && (col_base + 64 <= d.cols);
-  const uint32_t cg = d.cg0 + (col >> 3);
+  const bool copy = d.p1 != nullptr;  // NULL: the pass-through is an alias
+  const uint32_t nbr = (d.rows + 31) >> 5;
+  const uint32_t by0 = byg * a.tiles_per_wg;
+  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
 
-  uint4 v[4];
-  int nv[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t row = row_base + r0 + 8 * i;
-    nv[i] = full ? 8 : valid_count(row, col, d.rows, d.cols);
-    v[i] = make_uint4(0, 0, 0, 0);
-    if (nv[i] > 0) v[i] = *(const uint4*)(g + (size_t)row * d.ld + col);
-  }
-
-  // sum_{b_l}(g .* R): every product is exact in fp32 (R in {0, +-1, +-2}); the
-  // order of the additions is fixed (i, then k, then the lane tree), so the
-  // result is reproducible bit for bit.
-  float acc = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (nv[i] == 0) continue;
-    const uint32_t row = row_base + r0 + 8 * i;
-    const uint32_t codes = group_codes(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
-    const uint32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const uint32_t code = (codes >> (4 * k)) & 0xFu;
-      const float mag = (float)(code & 3u);
-      const float r = __uint_as_float(__float_as_uint(mag) | ((code & 8u) << 28));
-      const float gv = __uint_as_float((k & 1) ? (e[k >> 1] & 0xFFFF0000u) : (e[k >> 1] << 16));
-      if (k < nv[i]) acc += gv * r;
+  Tile cur = load_tile(g, d, by0, col_base, col, r0);
+  for (uint32_t by = by0; by < by_end; ++by) {
+    Tile nxt;
+    const bool more = by + 1 < by_end;
+    if (more) nxt = load_tile(g, d, by + 1, col_base, col, r0);
+    if (cur.full) {
+      if (copy) bwd_tile<true, true>(a, d, cur, by, col_base, lane);
+      else bwd_tile<true, false>(a, d, cur, by, col_base, lane);
+    } else {
+      if (copy) bwd_tile<false, true>(a, d, cur, by, col_base, lane);
+      else bwd_tile<false, false>(a, d, cur, by, col_base, lane);
     }
-    if (dw != nullptr) {  // dL/dw = dL/dw_hat, bit for bit
-      uint16_t* dst = dw + (size_t)row * d.ld + col;
-      if (nv[i] == 8) {
-        *(uint4*)dst = v[i];
-      } else {
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-          if (k < nv[i]) dst[k] = (uint16_t)(e[k >> 1] >> ((k & 1) * 16));
-      }
-    }
-  }
-  acc = block_sum_f32(acc);
-
-  const uint32_t nbc = (d.cols + 31) >> 5;
-  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
-  if (bcol < nbc && (gc & 3) == 0 && r0 == 0) {
-    const float s32 = scale[(size_t)by * nbc + bcol];
-    const float neg_ln2 = __uint_as_float(0xBF317218u);  // -ln 2
-    dbt[(size_t)by * nbc + bcol] = (neg_ln2 * s32) * acc;
+    if (more) cur = nxt;
   }
 }
 
@@ -197,26 +252,26 @@ __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict_
   const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (uint64_t)rows * ngrp) return;
   const uint32_t row = (uint32_t)(idx / ngrp), cgl = (uint32_t)(idx % ngrp);
-  out[idx] = group_codes(cg0 + cgl, row0 + row, step_lo, step_hi, seed_lo, seed_hi);
+  out[idx] = packed_codes(group_noise(cg0 + cgl, row0 + row, step_lo, step_hi, seed_lo, seed_hi));
 }
 
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_tiles, int fmt, hipStream_t stream) {
-  if (n_tiles == 0) return GWS_OK;
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
   switch (fmt) {
-    case GWS_FMT_BF16: hipLaunchKernelGGL(sample_fwd_kernel<0>, dim3(n_tiles), dim3(kThreads), 0, stream, a); break;
-    case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL(sample_fwd_kernel<1>, dim3(n_tiles), dim3(kThreads), 0, stream, a); break;
-    case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL(sample_fwd_kernel<2>, dim3(n_tiles), dim3(kThreads), 0, stream, a); break;
+    case GWS_FMT_BF16: hipLaunchKernelGGL(sample_fwd_kernel<0>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+    case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL(sample_fwd_kernel<1>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+    case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL(sample_fwd_kernel<2>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
     default: return GWS_ERR_FORMAT;
   }
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
-int launch_sample_bwd(const LaunchArgs& a, uint32_t n_tiles, hipStream_t stream) {
-  if (n_tiles == 0) return GWS_OK;
-  hipLaunchKernelGGL(sample_bwd_kernel, dim3(n_tiles), dim3(kThreads), 0, stream, a);
+int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
+  hipLaunchKernelGGL(sample_bwd_kernel, dim3(n_wg), dim3(kThreads), 0, stream, a);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
