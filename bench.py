@@ -24,6 +24,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense BF16, published
 FWD_BYTES_PER_PARAM = 4.0      # read w (2) + write w_hat (2); + 8 B per 1024-param block (b_t, scale)
 BWD_BYTES_PER_PARAM = 2.0      # read dL/dw_hat (2); dL/dw aliased; + 8 B per block (scale, db_t)
 BLOCK_BYTES = 8.0
+# HBM bytes per sample_fwd_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (KiB per dispatch, FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0: the factors a 1 GiB plain device
+# copy gives in the same runs).  Summaries: profiles/sample_kernels_<workload>.md.
+MEASURED_FWD_TRAFFIC_BYTES = {"gpt2_124m": 341498329, "llama_1b": 1298625865}
 
 
 def parse():
@@ -143,12 +147,7 @@ def main():
         "paper_context": "paper reports 1.40% end-to-end tokens/s overhead (Llama2-134M, A100-40G, Table 1); "
                          "no params/s or GB/s figure exists for this path",
     }
-    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file):
-        try:
-            out["roofline"]["traffic"] = json.load(open(traffic_file)).get(args.workload)
-        except Exception:
-            pass
+    out["roofline"]["traffic"] = MEASURED_FWD_TRAFFIC_BYTES.get(args.workload)
 
     # ---- cpu_baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     if not args.no_cpu:
