@@ -16,7 +16,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-SOURCES = ["gws_api.hip", "gws_sample.hip", "gws_linear.hip"]
+SOURCES = ["gws_api.hip", "gws_sample.hip", "gws_linear.hip", "gws_gemm256.hip"]
 HEADERS = ["gws_device.h", "gws_launch.h"]
 OUT = os.path.join(_HERE, "libgws.so")
 

@@ -58,5 +58,7 @@ struct GemmArgs {
   uint32_t row0, cg0, seed_lo, seed_hi, step_lo, step_hi;
 };
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
+bool gemm256_applicable(const GemmArgs& g);
+int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
 
 }  // namespace gws

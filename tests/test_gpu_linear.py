@@ -102,6 +102,29 @@ def test_plain_gemm_vs_fp64():
     check_y(synth.bits(y2), synth.bits(x), synth.bits(wt), True)
 
 
+@pytest.mark.parametrize("w_is_nk", [False, True])
+def test_plain_gemm_large_tile_path(w_is_nk):
+    # M, N multiples of 256 and K of 64 take the 256x256x64 kernel; 768 x 1280 = 3 x 5 tiles
+    # exercises the XCD / patch tile numbering with a short last band
+    M, K, N = 768, 192, 1280
+    x = synth.make_activation(2, M, K)
+    w = synth.make_tensor(2, K, N, with_grad=False)["w"]
+    wd = (w.t().contiguous() if w_is_nk else w).to(DEV)
+    y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(x.to(DEV), wd, y, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y), synth.bits(x), synth.bits(wd.cpu()), w_is_nk)
+    # a 9 x 2 tile grid: more than one band of 8 m-tiles
+    M2, K2, N2 = 2304, 64, 512
+    x2 = synth.make_activation(3, M2, K2)
+    w2 = synth.make_tensor(3, K2, N2, with_grad=False)["w"]
+    wd2 = (w2.t().contiguous() if w_is_nk else w2).to(DEV)
+    y2 = torch.zeros(M2, N2, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(x2.to(DEV), wd2, y2, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y2), synth.bits(x2), synth.bits(wd2.cpu()), w_is_nk)
+
+
 def test_config5_fused_linear_8192x2048x5632_sampled_rows():
     M, K, N = 8192, 2048, 5632
     rows_sel = np.array([0, 1, 31, 127, 128, 4095, 4096, 8000, 8191])
