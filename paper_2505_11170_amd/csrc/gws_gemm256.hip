@@ -17,7 +17,10 @@
 // (workgroups are dealt round-robin to the 8 XCDs, each with its own L2) form an
 // 8 x 4 patch that shares 8 X panels and 4 W panels.
 // The epilogue stages the BF16 result in LDS and writes 16 bytes per lane.
+#include <atomic>
+
 #include "gws_launch.h"
+#include "gws_sample_tile.h"
 
 namespace gws {
 
@@ -44,10 +47,12 @@ union Frag8 {
   i16x4 h[2];
 };
 
+// One 256 x 256 output tile.  `L` is the launch-order tile number (remapped below),
+// `wsrc` the weight operand (W, or the sampled w_hat).
 template <bool W_NK>
-__global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
+__device__ __forceinline__ void gemm256_tile(const GemmArgs& g, const uint16_t* __restrict__ wsrc, uint32_t L,
+                                             uint16_t* lds) {
   using namespace g256;
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   uint16_t* const As = lds;                                   // [2][TM][PA]
   uint16_t* const Bs = lds + 2 * A_STAGE;                     // [2][...]
   constexpr int B_STAGE = W_NK ? B_STAGE_NK : B_STAGE_KN;
@@ -57,7 +62,6 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
 
   // ---- tile numbering: XCD-contiguous ranges of an (8 m x 4 n)-patch order ----
   const uint32_t mt = g.M / TM, nt = g.N / TN, total = mt * nt;
-  uint32_t L = blockIdx.x;
   {
     const uint32_t per = total / 8, rem = total % 8, x = L % 8, j = L / 8;
     // XCD x owns `per` tiles (+1 for the first `rem`); its range starts at:
@@ -76,8 +80,8 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
   // ---- global -> register staging: 8 + 8 sixteen-byte chunks per thread ----
   const uint16_t* a_src = g.x + (size_t)(m0 + (tid >> 3)) * g.ldx + (tid & 7) * 8;   // + 32 rows per i
   const uint16_t* b_src;
-  if (W_NK) b_src = g.w + (size_t)(n0 + (tid >> 3)) * g.ldw + (tid & 7) * 8;           // + 32 rows per i
-  else b_src = g.w + (size_t)(tid >> 5) * g.ldw + n0 + (tid & 31) * 8;                 // + 8 k-rows per i
+  if (W_NK) b_src = wsrc + (size_t)(n0 + (tid >> 3)) * g.ldw + (tid & 7) * 8;          // + 32 rows per i
+  else b_src = wsrc + (size_t)(tid >> 5) * g.ldw + n0 + (tid & 31) * 8;                // + 8 k-rows per i
   u32x4 ra[8], rb[8];
   auto load_global = [&](uint32_t kt) {
 #pragma unroll
@@ -171,6 +175,109 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
   }
 }
 
+template <bool W_NK>
+__global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  gemm256_tile<W_NK>(g, g.w, blockIdx.x, lds);
+}
+
+// ---------------------------------------------------------------------------
+// Fused sampled-weight linear, sample-once form.  A persistent grid (one
+// workgroup per compute unit) first samples W cooperatively: every wavefront
+// takes 32x32 blocks of the stored matrix round-robin (paper Eq. 3 + cast, as in
+// the forward kernel), writes w_hat and scale, and the grid meets at one
+// device-wide arrival counter.  The tiles of the GEMM then read w_hat through
+// L2 like a plain weight.  Each block is sampled once, instead of once per
+// M-tile as when the sampling sits in the operand load itself.
+//
+// Synchronisation state lives in two device words.  The arrival counter resets
+// itself; the epoch word is compared with a per-call epoch, so stale values of
+// earlier calls never match.  The wait is bounded: a workgroup that gives up
+// (e.g. because not all workgroups are resident) samples every block itself,
+// which produces the same bytes.  Calls that overlap in time on one GPU would
+// share the two words and must not be issued concurrently.
+// ---------------------------------------------------------------------------
+__device__ uint32_t g_fused_arrive = 0;
+__device__ uint32_t g_fused_epoch = 0;
+
+// The stored weight seen as the forward kernel sees it: 32-row x 256-column
+// workgroup tiles of four wavefront tiles (32 x 64, two blocks each).  Wavefront
+// tile t covers block row t / (cols/64), columns 64 * (t % (cols/64)).  A batch of
+// kDepth tiles is loaded before the first is computed, so the single wavefront per
+// SIMD pays the memory latency once per batch; neighbouring wavefronts take
+// neighbouring tiles, so a workgroup reads 512 contiguous bytes per row.
+template <int FMT>
+__device__ __forceinline__ void sample_tiles(const GemmArgs& g, const TileDesc& d, uint32_t first, uint32_t stride,
+                                             uint32_t lane) {
+  constexpr int kDepth = 3;
+  const uint32_t per_row = d.cols >> 6, ntiles = (d.rows >> 5) * per_row;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  for (uint32_t base = first; base < ntiles; base += kDepth * stride) {
+    Tile t[kDepth];
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) {
+      const uint32_t id = base + j * stride;
+      if (id < ntiles) {
+        const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
+        t[j] = load_tile((const uint16_t*)d.p0, d, by, cb, cb + gc * 8, r0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) {
+      const uint32_t id = base + j * stride;
+      if (id < ntiles) {
+        const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
+        fwd_tile<FMT, true, false>(g.step_lo, g.step_hi, d, t[j], by, cb, lane);
+      }
+    }
+  }
+}
+
+template <int FMT, bool W_NK>
+__global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs g, const uint32_t epoch) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  __shared__ uint32_t gave_up;
+  const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  TileDesc d;  // the stored weight as the forward pass describes it (cols is a multiple of 64 here)
+  d.p0 = g.w; d.p1 = g.w_hat; d.p2 = (void*)g.bt; d.p3 = g.scale;
+  d.rows = W_NK ? g.N : g.K; d.cols = W_NK ? g.K : g.N; d.ld = g.ldw;
+  d.row0 = g.row0; d.cg0 = g.cg0; d.seed_lo = g.seed_lo; d.seed_hi = g.seed_hi; d.tiles_x = 0;
+
+  // ---- phase 1: sample W once, all wavefronts of the grid ----
+  sample_tiles<FMT>(g, d, blockIdx.x * 4 + wave, gridDim.x * 4, lane);
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();  // release: this workgroup's w_hat / scale stores are visible device-wide
+    const uint32_t old = __hip_atomic_fetch_add(&g_fused_arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == gridDim.x - 1) {  // last to arrive: reset the counter, publish the epoch
+      __hip_atomic_store(&g_fused_arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&g_fused_epoch, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // poll with relaxed loads (an acquire load would invalidate caches on every poll,
+    // under the feet of the workgroups still sampling); acquire once at the end
+    uint32_t spins = 0, failed = 0;
+    while (__hip_atomic_load(&g_fused_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+      if (++spins > 100000u) { failed = 1; break; }  // bounded wait (about 0.1 s)
+      __builtin_amdgcn_s_sleep(32);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    gave_up = failed;
+  }
+  __syncthreads();
+  if (gave_up) {  // not every workgroup arrived in time: sample everything here (same bytes)
+    sample_tiles<FMT>(g, d, wave, 4, lane);
+    __threadfence();
+    __syncthreads();
+  }
+
+  // ---- phase 2: GEMM tiles on w_hat ----
+  const uint32_t total = (g.M / g256::TM) * (g.N / g256::TN);
+  for (uint32_t L = blockIdx.x; L < total; L += gridDim.x) {
+    gemm256_tile<W_NK>(g, g.w_hat, L, lds);
+    __syncthreads();  // the epilogue staging is read before the next tile overwrites it
+  }
+}
+
 bool gemm256_applicable(const GemmArgs& g) {
   return g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 && g.M > 0 && g.N > 0 && g.K > 0;
 }
@@ -190,6 +297,46 @@ int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream) {
     hipLaunchKernelGGL(gemm256_kernel<false>, dim3((uint32_t)tiles), dim3(256), lds, stream, g);
   }
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+template <int FMT>
+static int launch_fused_fmt(const GemmArgs& g, int w_is_nk, uint32_t grid, size_t lds, uint32_t epoch, hipStream_t s) {
+  hipError_t e;
+  if (w_is_nk) {
+    e = hipFuncSetAttribute((const void*)linear256_fused_kernel<FMT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    hipLaunchKernelGGL((linear256_fused_kernel<FMT, true>), dim3(grid), dim3(256), lds, s, g, epoch);
+  } else {
+    e = hipFuncSetAttribute((const void*)linear256_fused_kernel<FMT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    hipLaunchKernelGGL((linear256_fused_kernel<FMT, false>), dim3(grid), dim3(256), lds, s, g, epoch);
+  }
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+bool linear256_fused_applicable(const GemmArgs& g) {
+  return gemm256_applicable(g) && g.w_hat != nullptr && g.scale != nullptr;
+}
+
+int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream) {
+  // one workgroup per compute unit: the whole grid is resident, so the arrival counter completes
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return n;
+  }();
+  if (cus <= 0) return GWS_ERR_LAUNCH;
+  static std::atomic<uint32_t> next_epoch{1};
+  uint32_t epoch = next_epoch.fetch_add(1);
+  if (epoch == 0) epoch = next_epoch.fetch_add(1);
+  const size_t lds = g256::lds_bytes(w_is_nk != 0);
+  switch (fmt) {
+    case GWS_FMT_BF16: return launch_fused_fmt<0>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
+    case GWS_FMT_FP8_E4M3: return launch_fused_fmt<1>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
+    case GWS_FMT_FP6_E3M2: return launch_fused_fmt<2>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
+    default: return GWS_ERR_FORMAT;
+  }
 }
 
 }  // namespace gws

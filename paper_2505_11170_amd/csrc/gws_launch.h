@@ -60,5 +60,7 @@ struct GemmArgs {
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
+bool linear256_fused_applicable(const GemmArgs& g);
+int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream);
 
 }  // namespace gws

@@ -1,0 +1,129 @@
+// Wavefront-tile building blocks of the forward pass (paper Eq. 3 + cast), shared by
+// the elementwise kernel and the sampling prologue of the fused linear.
+// Internal to csrc/.
+#pragma once
+
+#include "gws_launch.h"
+
+namespace gws {
+
+// Valid elements of the 16-byte group at (row, col): 8, fewer at a ragged right
+// edge, 0 outside.
+__device__ __forceinline__ int valid_count(uint32_t row, uint32_t col, uint32_t rows, uint32_t cols) {
+  if (row >= rows || col >= cols) return 0;
+  const uint32_t left = cols - col;
+  return left >= 8 ? 8 : (int)left;
+}
+
+__device__ __forceinline__ u32x4 load16(const uint16_t* p) {
+  return __builtin_nontemporal_load((const u32x4*)p);
+}
+__device__ __forceinline__ void store16(uint16_t* p, const u32x4 v) {
+  __builtin_nontemporal_store(v, (u32x4*)p);
+}
+
+// Zero the elements of a group that lie past the right edge (nv valid of 8).
+__device__ __forceinline__ u32x4 mask_group(u32x4 v, int nv) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k >= nv) v[k >> 1] &= (k & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+  return v;
+}
+
+__device__ __forceinline__ void store_partial(uint16_t* dst, const u32x4 v, int nv) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (k < nv) dst[k] = (uint16_t)(v[k >> 1] >> ((k & 1) * 16));
+}
+
+// The four 16-byte groups a lane holds of one wavefront tile.
+struct Tile {
+  u32x4 v[4];
+  int nv[4];   // valid elements per group (8 everywhere on a full tile)
+  bool full;   // the 32x64 tile lies inside the tensor: no validity tests needed
+};
+
+// A 16-byte load never leaves its row: ld % 8 == 0 and ld >= cols.
+__device__ __forceinline__ Tile load_tile(const uint16_t* __restrict__ src, const TileDesc& d, uint32_t by,
+                                          uint32_t col_base, uint32_t col, uint32_t r0) {
+  Tile t;
+  const uint32_t row_base = by * 32;
+  t.full = (row_base + 32 <= d.rows) && (col_base + 64 <= d.cols);
+  if (t.full) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      t.nv[i] = 8;
+      t.v[i] = load16(src + (size_t)(row_base + r0 + 8 * i) * d.ld + col);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t row = row_base + r0 + 8 * i;
+      t.nv[i] = valid_count(row, col, d.rows, d.cols);
+      t.v[i] = u32x4{0, 0, 0, 0};
+      if (t.nv[i] > 0) t.v[i] = load16(src + (size_t)row * d.ld + col);
+    }
+  }
+  return t;
+}
+
+// STREAM: w_hat is written with streaming (non-temporal) stores, right for a pass
+// that is not consumed at once; off, the stores stay in cache for a reader that follows.
+template <int FMT, bool FULL, bool STREAM = true>
+__device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
+                                         uint32_t by, uint32_t col_base, uint32_t lane) {
+  const uint32_t row_base = by * 32;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const uint32_t col = col_base + gc * 8;
+  uint16_t* __restrict__ w_hat = (uint16_t*)d.p1;
+  const float* __restrict__ bt = (const float*)d.p2;
+  float* __restrict__ scale = (float*)d.p3;
+
+  if (!FULL) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (t.nv[i] < 8) t.v[i] = mask_group(t.v[i], t.nv[i]);  // elements past cols do not exist
+  }
+
+  // ---- a = max_{b_l}|w| on the magnitude bits (exact) ----
+  uint32_t m = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) m = absmax_pk(t.v[i], m);
+  m = max(m & 0xFFFFu, m >> 16);
+  const uint32_t a16 = block_max_u32(m);
+
+  // ---- per-block scale ----
+  const uint32_t nbc = (d.cols + 31) >> 5;
+  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
+  const bool block_exists = FULL || bcol < nbc;
+  const float btv = block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f;
+  BlockScale b = block_scale(a16, btv);
+  if (FMT == 1) cast_constants<8, -6>(a16, b);
+  if (FMT == 2) cast_constants<4, -2>(a16, b);
+  if (block_exists && (gc & 3) == 0 && r0 == 0) scale[(size_t)by * nbc + bcol] = b.s32;
+  // hardware FP8 converters only if neither block of this wavefront can overflow
+  const bool hw = (FMT == 1) && (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0);
+
+  // ---- noise, add, round, cast, store ----
+  const uint32_t cg = d.cg0 + (col >> 3);
+  auto finish = [&](bool use_hw) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (!FULL && t.nv[i] == 0) continue;
+      const uint32_t row = row_base + r0 + 8 * i;
+      const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
+      uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+      if (FULL || t.nv[i] == 8) {
+        if (STREAM) store16(dst, o);
+        else *(u32x4*)dst = o;
+      } else {
+        store_partial(dst, o, t.nv[i]);
+      }
+    }
+  };
+  if (FMT == 1 && hw) finish(true);
+  else finish(false);
+}
+
+}  // namespace gws

@@ -125,6 +125,19 @@ def test_plain_gemm_large_tile_path(w_is_nk):
     check_y(synth.bits(y2), synth.bits(x2), synth.bits(wd2.cpu()), w_is_nk)
 
 
+@pytest.mark.parametrize("w_is_nk", [False, True])
+@pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
+def test_linear_sample_once_path(w_is_nk, fmt):
+    # M, N multiples of 256, K of 64 and w_hat requested: cooperative sampling prologue + GEMM on w_hat
+    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2)
+    run_case(256, 64, 256, w_is_nk, fmt, bt=3.0, seed_id=8)
+
+
+def test_linear_sample_once_repeated_calls_reuse_the_sync_words():
+    for step in range(4):
+        run_case(512, 192, 512, False, gws.FMT_FP8_E4M3, seed_id=9, step=step)
+
+
 def test_config5_fused_linear_8192x2048x5632_sampled_rows():
     M, K, N = 8192, 2048, 5632
     rows_sel = np.array([0, 1, 31, 127, 128, 4095, 4096, 8000, 8191])
