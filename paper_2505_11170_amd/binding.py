@@ -12,7 +12,7 @@ from dataclasses import dataclass
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libgws.so")
+_LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 

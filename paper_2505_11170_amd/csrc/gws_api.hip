@@ -64,12 +64,15 @@ inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
 // Pack descriptors into as few launches as the kernel-argument segment and the
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 int run_batched(const gws_tensor* t, int n, bool fwd, int fmt, uint64_t step, hipStream_t stream) {
-  // Longer walks per workgroup hide more latency but leave fewer workgroups to
-  // balance over the 256 compute units: keep at least ~16 per unit.
+  // Block rows per workgroup.  Forward: 1 (most workgroups, fewest registers).  Backward
+  // does less per tile, so a workgroup takes up to 8 while at least ~20 workgroups per
+  // compute unit remain to balance the 256 units.
   uint64_t total = 0;
   for (int i = 0; i < n; ++i)
     if (t[i].rows > 0 && t[i].cols > 0) total += wg_count(t[i], 1);
-  const uint32_t per_wg = total >= 16384 ? 4u : (total >= 8192 ? 2u : 1u);
+  uint32_t per_wg = 1;
+  if (!fwd)
+    while (per_wg < 8 && total / (2 * per_wg) >= 5000) per_wg *= 2;
 
   LaunchArgs a;
   memset(&a, 0, sizeof a);

@@ -8,8 +8,10 @@
 // sit side by side (512 contiguous bytes per row), and the per-block reductions
 // (absmax, sum of g.*R) stay inside one wavefront: no LDS, no barrier.
 // A workgroup walks down `tiles_per_wg` consecutive block rows of its 256-column
-// strip and issues the loads of the next tile before it computes the current
-// one, so a wavefront hides most of its own memory latency.
+// strip (1 in the forward pass, up to 8 in the lighter backward pass, where the
+// per-workgroup set-up would otherwise show).  Latency is hidden by occupancy:
+// measured on MI355X, keeping the next tile's loads in flight inside a wavefront
+// costs more in registers than it gains.
 // One Philox4x32-10 call yields the 16 bits x 8 elements of one 16-byte group,
 // so the noise lives only in registers (2 bytes per parameter of HBM traffic per
 // operand, Sec. 3.5; the 0.5 byte per parameter temporary of the paper is gone).
@@ -52,14 +54,13 @@ __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a
   const uint32_t by0 = byg * a.tiles_per_wg;
   const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
 
-  Tile cur = load_tile(w, d, by0, col_base, col, r0);
-  for (uint32_t by = by0; by < by_end; ++by) {
-    Tile nxt;
-    const bool more = by + 1 < by_end;
-    if (more) nxt = load_tile(w, d, by + 1, col_base, col, r0);  // in flight during the compute below
-    if (cur.full) fwd_tile<FMT, true>(a.step_lo, a.step_hi, d, cur, by, col_base, lane);
-    else fwd_tile<FMT, false>(a.step_lo, a.step_hi, d, cur, by, col_base, lane);
-    if (more) cur = nxt;
+  // first tile loaded ahead of the loop: the common one-tile case stays straight-line code
+  Tile t = load_tile(w, d, by0, col_base, col, r0);
+  for (uint32_t by = by0;;) {
+    if (t.full) fwd_tile<FMT, true>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    else fwd_tile<FMT, false>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    if (++by >= by_end) break;
+    t = load_tile(w, d, by, col_base, col, r0);
   }
 }
 
@@ -117,19 +118,17 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a
   const uint32_t by0 = byg * a.tiles_per_wg;
   const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
 
-  Tile cur = load_tile(g, d, by0, col_base, col, r0);
-  for (uint32_t by = by0; by < by_end; ++by) {
-    Tile nxt;
-    const bool more = by + 1 < by_end;
-    if (more) nxt = load_tile(g, d, by + 1, col_base, col, r0);
-    if (cur.full) {
-      if (copy) bwd_tile<true, true>(a, d, cur, by, col_base, lane);
-      else bwd_tile<true, false>(a, d, cur, by, col_base, lane);
+  Tile t = load_tile(g, d, by0, col_base, col, r0);
+  for (uint32_t by = by0;;) {
+    if (t.full) {
+      if (copy) bwd_tile<true, true>(a, d, t, by, col_base, lane);
+      else bwd_tile<true, false>(a, d, t, by, col_base, lane);
     } else {
-      if (copy) bwd_tile<false, true>(a, d, cur, by, col_base, lane);
-      else bwd_tile<false, false>(a, d, cur, by, col_base, lane);
+      if (copy) bwd_tile<false, true>(a, d, t, by, col_base, lane);
+      else bwd_tile<false, false>(a, d, t, by, col_base, lane);
     }
-    if (more) cur = nxt;
+    if (++by >= by_end) break;
+    t = load_tile(g, d, by, col_base, col, r0);
   }
 }
 
