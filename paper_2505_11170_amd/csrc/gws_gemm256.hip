@@ -190,15 +190,55 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
 // L2 like a plain weight.  Each block is sampled once, instead of once per
 // M-tile as when the sampling sits in the operand load itself.
 //
-// Synchronisation state lives in two device words.  The arrival counter resets
-// itself; the epoch word is compared with a per-call epoch, so stale values of
-// earlier calls never match.  The wait is bounded: a workgroup that gives up
+// Synchronisation state lives in a few device words.  The arrival counters reset
+// themselves; the epoch and flag words are compared with a per-call epoch, so stale
+// values of earlier calls never match.  The wait is bounded: a workgroup that gives up
 // (e.g. because not all workgroups are resident) samples every block itself,
 // which produces the same bytes.  Calls that overlap in time on one GPU would
 // share the two words and must not be issued concurrently.
 // ---------------------------------------------------------------------------
-__device__ uint32_t g_fused_arrive = 0;
+// Eight arrival groups (workgroup index mod 8: one per XCD when workgroups are dealt
+// round-robin), each with its own counter and flag on its own 128-byte line, and one
+// top-level counter for the eight group leaders.  Far fewer workgroups then contend for,
+// and poll, any one address than with a single flat counter.
+__device__ uint32_t g_fused_group_arrive[8 * 32];
+__device__ uint32_t g_fused_group_flag[8 * 32];
+__device__ uint32_t g_fused_top_arrive = 0;
 __device__ uint32_t g_fused_epoch = 0;
+
+// Returns true when every workgroup of the grid has arrived (and their earlier stores
+// are visible), false when the bounded wait ran out.  Called by one thread per workgroup.
+__device__ __forceinline__ bool grid_arrive_and_wait(uint32_t epoch) {
+  const uint32_t grp = blockIdx.x & 7u;
+  const uint32_t members = (gridDim.x >> 3) + ((grp < (gridDim.x & 7u)) ? 1u : 0u);
+  const uint32_t groups = gridDim.x < 8u ? gridDim.x : 8u;
+  __threadfence();  // release: this workgroup's w_hat / scale stores are visible device-wide
+  uint32_t spins = 0;
+  const uint32_t old = __hip_atomic_fetch_add(&g_fused_group_arrive[grp * 32], 1u, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+  if (old == members - 1) {  // last of its group: reset the counter, arrive at the top level
+    __hip_atomic_store(&g_fused_group_arrive[grp * 32], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t t = __hip_atomic_fetch_add(&g_fused_top_arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == groups - 1) {
+      __hip_atomic_store(&g_fused_top_arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&g_fused_epoch, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // polls are relaxed loads (an acquire load would invalidate caches on every poll, under
+    // the feet of the workgroups still sampling); one acquire fence follows the wait
+    while (__hip_atomic_load(&g_fused_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+      if (++spins > 200000u) return false;  // bounded wait (about 0.1 s)
+      __builtin_amdgcn_s_sleep(4);
+    }
+    __hip_atomic_store(&g_fused_group_flag[grp * 32], epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    while (__hip_atomic_load(&g_fused_group_flag[grp * 32], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+      if (++spins > 100000u) return false;
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  return true;
+}
 
 // The stored weight seen as the forward kernel sees it: 32-row x 256-column
 // workgroup tiles of four wavefront tiles (32 x 64, two blocks each).  Wavefront
@@ -246,23 +286,7 @@ __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs 
   // ---- phase 1: sample W once, all wavefronts of the grid ----
   sample_tiles<FMT>(g, d, blockIdx.x * 4 + wave, gridDim.x * 4, lane);
   __syncthreads();
-  if (tid == 0) {
-    __threadfence();  // release: this workgroup's w_hat / scale stores are visible device-wide
-    const uint32_t old = __hip_atomic_fetch_add(&g_fused_arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == gridDim.x - 1) {  // last to arrive: reset the counter, publish the epoch
-      __hip_atomic_store(&g_fused_arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&g_fused_epoch, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    // poll with relaxed loads (an acquire load would invalidate caches on every poll,
-    // under the feet of the workgroups still sampling); acquire once at the end
-    uint32_t spins = 0, failed = 0;
-    while (__hip_atomic_load(&g_fused_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
-      if (++spins > 100000u) { failed = 1; break; }  // bounded wait (about 0.1 s)
-      __builtin_amdgcn_s_sleep(32);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    gave_up = failed;
-  }
+  if (tid == 0) gave_up = grid_arrive_and_wait(epoch) ? 0u : 1u;
   __syncthreads();
   if (gave_up) {  // not every workgroup arrived in time: sample everything here (same bytes)
     sample_tiles<FMT>(g, d, wave, 4, lane);
