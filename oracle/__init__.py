@@ -34,48 +34,52 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def configure(L: ctypes.CDLL) -> ctypes.CDLL:
+    """Declare the argument types of every entry point on a loaded oracle library."""
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    vp, i64, u64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+    L.gwso_set_threads.argtypes = [ci]
+    L.gwso_set_threads.restype = ci
+    L.gwso_philox4x32.argtypes = [u32p, u32p, ci, u32p]
+    L.gwso_philox4x32.restype = None
+    L.gwso_derive_seed.argtypes = [u64, u64]
+    L.gwso_derive_seed.restype = u64
+    L.gwso_nibbles_to_code.argtypes = [ctypes.c_uint] * 4
+    L.gwso_nibbles_to_code.restype = ci
+    L.gwso_code_to_r.argtypes = [ci]
+    L.gwso_code_to_r.restype = ci
+    L.gwso_element_nibble.argtypes = [ci]
+    L.gwso_element_nibble.restype = ci
+    L.gwso_noise.argtypes = [i64, i64, i64, i64, u64, u64, vp, vp]
+    L.gwso_noise.restype = None
+    L.gwso_bf16_rne.argtypes = [ctypes.c_float]
+    L.gwso_bf16_rne.restype = ctypes.c_uint16
+    L.gwso_bf16_add.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
+    L.gwso_bf16_add.restype = ctypes.c_uint16
+    L.gwso_exp2.argtypes = [ctypes.c_float]
+    L.gwso_exp2.restype = ctypes.c_float
+    L.gwso_cast.argtypes = [ctypes.c_uint16, ci, ci]
+    L.gwso_cast.restype = ctypes.c_uint16
+    L.gwso_bf16_add_n.argtypes = [vp, vp, vp, i64]
+    L.gwso_bf16_add_n.restype = None
+    L.gwso_cast_n.argtypes = [vp, ci, ci, vp, i64]
+    L.gwso_cast_n.restype = None
+    L.gwso_exp2_n.argtypes = [vp, vp, i64]
+    L.gwso_exp2_n.restype = None
+    L.gwso_sample_fwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, u64, u64, vp, vp]
+    L.gwso_sample_fwd.restype = ci
+    L.gwso_sample_bwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, u64, u64, vp, vp, vp]
+    L.gwso_sample_bwd.restype = ci
+    L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
+    L.gwso_linear_fwd.restype = ci
+    return L
+
+
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
         build()
-        L = ctypes.CDLL(_LIB)
-        u32p = ctypes.POINTER(ctypes.c_uint32)
-        vp, i64, u64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
-        L.gwso_set_threads.argtypes = [ci]
-        L.gwso_set_threads.restype = ci
-        L.gwso_philox4x32.argtypes = [u32p, u32p, ci, u32p]
-        L.gwso_philox4x32.restype = None
-        L.gwso_derive_seed.argtypes = [u64, u64]
-        L.gwso_derive_seed.restype = u64
-        L.gwso_nibbles_to_code.argtypes = [ctypes.c_uint] * 4
-        L.gwso_nibbles_to_code.restype = ci
-        L.gwso_code_to_r.argtypes = [ci]
-        L.gwso_code_to_r.restype = ci
-        L.gwso_element_nibble.argtypes = [ci]
-        L.gwso_element_nibble.restype = ci
-        L.gwso_noise.argtypes = [i64, i64, i64, i64, u64, u64, vp, vp]
-        L.gwso_noise.restype = None
-        L.gwso_bf16_rne.argtypes = [ctypes.c_float]
-        L.gwso_bf16_rne.restype = ctypes.c_uint16
-        L.gwso_bf16_add.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
-        L.gwso_bf16_add.restype = ctypes.c_uint16
-        L.gwso_exp2.argtypes = [ctypes.c_float]
-        L.gwso_exp2.restype = ctypes.c_float
-        L.gwso_cast.argtypes = [ctypes.c_uint16, ci, ci]
-        L.gwso_cast.restype = ctypes.c_uint16
-        L.gwso_bf16_add_n.argtypes = [vp, vp, vp, i64]
-        L.gwso_bf16_add_n.restype = None
-        L.gwso_cast_n.argtypes = [vp, ci, ci, vp, i64]
-        L.gwso_cast_n.restype = None
-        L.gwso_exp2_n.argtypes = [vp, vp, i64]
-        L.gwso_exp2_n.restype = None
-        L.gwso_sample_fwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, u64, u64, vp, vp]
-        L.gwso_sample_fwd.restype = ci
-        L.gwso_sample_bwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, u64, u64, vp, vp, vp]
-        L.gwso_sample_bwd.restype = ci
-        L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
-        L.gwso_linear_fwd.restype = ci
-        _lib = L
+        _lib = configure(ctypes.CDLL(_LIB))
     return _lib
 
 

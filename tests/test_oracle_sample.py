@@ -93,6 +93,41 @@ def test_forward_real_bt_scale_within_2ulp_of_fp64():
     assert 4.0 <= bt.min() and bt.max() <= 9.0 and bt.std() > 1.0
 
 
+def test_block_absmax_sees_every_position_and_only_its_own_block():
+    # one large element moved through every position of the middle block of a 3 x 3 block grid:
+    # exactly that block's scale follows it (first/last rows and columns included)
+    rows = cols = 96
+    base = np.full((rows, cols), 2.0 ** -6)
+    bt = np.full((3, 3), 5.0, dtype=np.float32)
+    for i in list(range(32, 64, 3)) + [63]:
+        for j in list(range(32, 64, 5)) + [63]:
+            wv = base.copy()
+            wv[i, j] = -3.0
+            _, scale = oracle.sample_fwd(to_bits(wv), bt, oracle.FMT_BF16, 1, 0)
+            want = np.full((3, 3), 2.0 ** -6 * 2.0 ** -4, dtype=np.float32)
+            want[1, 1] = 3.0 * 2.0 ** -4
+            assert (scale == want).all(), (i, j)
+
+
+def test_pqn_step_is_the_bf16_rounding_of_the_scale():
+    # real-valued b_t: s32 is not BF16-representable, and the step actually added is
+    # bf16_rne(s32).  Where w = 0 the BF16-target output is exactly R * step.
+    rows, cols = 128, 160
+    t = synth.make_tensor(11, rows, cols, with_grad=False)
+    w = synth.bits(t["w"]).copy()
+    zero = np.zeros((rows, cols), dtype=bool)
+    zero[::2, 1::2] = True
+    w[zero] = 0
+    bt = t["bt"].numpy()
+    seed = 31337
+    q, scale = oracle.sample_fwd(w, bt, oracle.FMT_BF16, seed, 4)
+    r, _ = oracle.noise(rows, cols, seed, 4)
+    step = torch.from_numpy(scale).to(torch.bfloat16).float().numpy().astype(np.float64)   # torch: RNE
+    assert (step != scale.astype(np.float64)).mean() > 0.9          # the rounding matters in this test
+    want = r.astype(np.float64) * expand(step, rows, cols)
+    assert (bf16_val(q)[zero] == want[zero]).all()
+
+
 def _find(r, value, i_lim=32, j_lim=32):
     pos = np.argwhere(r[:i_lim, :j_lim] == value)
     assert len(pos), value
