@@ -27,14 +27,14 @@ BLOCK_BYTES = 8.0
 # HBM bytes per sample_fwd_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (KiB per dispatch, FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0: the factors a 1 GiB plain device
 # copy gives in the same runs).  Summaries: profiles/sample_kernels_<workload>.md.
-MEASURED_FWD_TRAFFIC_BYTES = {"gpt2_124m": 341498329, "llama_1b": 1298625865}
+MEASURED_FWD_TRAFFIC_BYTES = {"gpt2_124m": 341724368, "llama_1b": 1298616892}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="gpt2_124m", choices=["gpt2_124m", "llama_1b"])
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets rotated through (0 = auto)")
     ap.add_argument("--no-extras", action="store_true")
@@ -182,12 +182,12 @@ def main():
             other = synth.llama_1b_shapes() if args.workload == "gpt2_124m" else synth.gpt2_124m_shapes()
             name = "llama_1b" if args.workload == "gpt2_124m" else "gpt2_124m"
             op = sum(s.rows * s.cols for s in other)
-            r2 = run_workload(other, 10, 2, max(1, min(8, int(1.5e9 // (6 * op)) + 1)))
+            r2 = run_workload(other, 30, 10, max(1, min(8, int(1.5e9 // (6 * op)) + 1)))
             fb = FWD_BYTES_PER_PARAM * op + BLOCK_BYTES * r2["blocks"]
             bb = BWD_BYTES_PER_PARAM * op + BLOCK_BYTES * r2["blocks"]
-            extras[name] = {"params": op, "params_per_s": op * 10 / r2["wall_s"], "fwd_ms": r2["fwd_ms"],
+            extras[name] = {"params": op, "params_per_s": op * 30 / r2["wall_s"], "fwd_ms": r2["fwd_ms"],
                             "bwd_ms": r2["bwd_ms"], "fwd_GBps": fb / r2["fwd_ms"] / 1e6, "bwd_GBps": bb / r2["bwd_ms"] / 1e6,
-                            "step_frac_of_hbm_peak": (fb + bb) / (r2["wall_s"] / 10) / 1e9 / HBM_PEAK_GBS}
+                            "step_frac_of_hbm_peak": (fb + bb) / (r2["wall_s"] / 30) / 1e9 / HBM_PEAK_GBS}
             del r2
             torch.cuda.empty_cache()
         except Exception as e:  # pragma: no cover
