@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets rotated through (0 = auto)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="run only the precision x format sweep of config 4 and print its JSON")
     ap.add_argument("--only-linear", action="store_true",
                     help="run only the fused-linear comparison (config 5) and print its JSON (for profiling)")
     ap.add_argument("--calibrate", action="store_true",
@@ -111,6 +113,25 @@ def main():
 
     if args.only_linear:
         print(json.dumps({"fused_linear": linear_bench(torch, gws, synth, dev)}))
+        return
+
+    if args.sweep:
+        # config 4: noise precision {4..9, U[4,9]} x target {FP6-E3M2, FP8-E4M3, BF16} on the 1B weights
+        shapes4 = synth.llama_1b_shapes()
+        p4 = sum(s.rows * s.cols for s in shapes4)
+        cells = {}
+        for fmt_name, fmt in (("fp6_e3m2", gws.FMT_FP6_E3M2), ("fp8_e4m3", gws.FMT_FP8_E4M3), ("bf16", gws.FMT_BF16)):
+            for bt in (4.0, 5.0, 6.0, 7.0, 8.0, 9.0, None):
+                r4 = run_workload(shapes4, 20, 5, 1, fmt=fmt, bt=bt)
+                fb = FWD_BYTES_PER_PARAM * p4 + BLOCK_BYTES * r4["blocks"]
+                bb = BWD_BYTES_PER_PARAM * p4 + BLOCK_BYTES * r4["blocks"]
+                cells[f"{fmt_name}/bt={'U[4,9]' if bt is None else int(bt)}"] = {
+                    "params_per_s": p4 * 20 / r4["wall_s"], "fwd_ms": r4["fwd_ms"], "bwd_ms": r4["bwd_ms"],
+                    "fwd_GBps": fb / r4["fwd_ms"] / 1e6, "bwd_GBps": bb / r4["bwd_ms"] / 1e6,
+                    "step_frac_of_hbm_peak": (fb + bb) / (r4["wall_s"] / 20) / 1e9 / HBM_PEAK_GBS}
+                del r4
+                torch.cuda.empty_cache()
+        print(json.dumps({"config4_sweep": cells}))
         return
 
     shapes = synth.gpt2_124m_shapes() if args.workload == "gpt2_124m" else synth.llama_1b_shapes()

@@ -151,6 +151,22 @@ def test_shard_origin_reproduces_full_tensor_noise():
     assert (s_sub == s_full[r0 // 32:, c0 // 32:c0 // 32 + 4]).all()
 
 
+def test_large_extents_and_origins():
+    # long thin tensors (2^20 rows or columns) and shard origins near the 32-bit limits of the
+    # noise counter: row index and column-group index wrap the same way on both sides
+    for rows, cols in ((32, 1 << 20), (1 << 20, 32)):
+        t = synth.make_tensor(70, rows, cols, with_grad=True)
+        item = dict(w=t["w"], bt=t["bt"], g=t["g"], rows=rows, cols=cols, seed=oracle.derive_seed(5, 70))
+        outs = check_forward([item], gws.FMT_FP8_E4M3, 2 ** 40 + 7)
+        item["scale"] = outs[0][1]
+        check_backward([item], 2 ** 40 + 7)
+    t = synth.make_tensor(71, 64, 128, with_grad=False)
+    for row0, col0 in ((2 ** 32 - 64 - 32, 0), (0, 8 * (2 ** 32 - 1) - 128 - 8 * 3), (2 ** 31, 2 ** 33)):
+        col0 -= col0 % 32
+        item = dict(w=t["w"], bt=t["bt"], rows=64, cols=128, seed=99, row0=row0, col0=col0)
+        check_forward([item], gws.FMT_BF16, 1)
+
+
 def test_determinism_and_step_dependence():
     items = make_items([(256, 512)], base=50)
     a = gpu_forward(items, gws.FMT_FP8_E4M3, 4)[0][0][0]
