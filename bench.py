@@ -52,7 +52,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the GaussWS hot path needs no exchange "
-              "between GPUs; see DESIGN.md, 'More than one GPU'). Use --gpus 1.", file=sys.stderr)
+              "between GPUs: blocks are independent and shards reproduce the noise from their origin). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

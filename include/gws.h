@@ -3,7 +3,8 @@
  *
  * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
  * every other pointer is host memory.  The library allocates no device memory,
- * keeps no global state and is thread-safe.  All GPU work is enqueued
+ * keeps no global state (one exception is stated at gws_linear_fwd) and is
+ * thread-safe.  All GPU work is enqueued
  * asynchronously on the given stream (a hipStream_t passed as void*, NULL = the
  * default stream); no call synchronises.  The return value is a gws_status and
  * reports argument and launch errors only; on any error nothing has been
@@ -100,19 +101,22 @@ int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* str
 int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream);
 
 /* Fused sampled-weight linear: Y = X * w_hat with w_hat produced as in
- * gws_sample_fwd inside the GEMM's weight-operand path (the paper, Sec. 3.5
- * "Separate kernels", keeps these apart; this is the fused alternative).
+ * gws_sample_fwd inside the GEMM kernel (the paper, Sec. 3.5 "Separate kernels",
+ * keeps sampling and matmul apart; this is the fused alternative).
  *   x : device BF16 [M x K], leading dimension ldx
  *   w : one descriptor (host).  w->w is [K x N] (rows = K, cols = N) or, when
  *       w_is_nk != 0, [N x K] (rows = N, cols = K; Y = X * w_hat^T).
  *       w->w_hat and w->scale are written if non-NULL (both or neither).
  *   y : device BF16 [M x N], leading dimension ldy; fp32 accumulation, one
  *       round-to-nearest-even to BF16.
- * K and N must be multiples of 32; ldx, ldy multiples of 8.                       */
-int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
-                   const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
-                   void* y, int64_t ldy, void* stream);
-
+ * K and N must be multiples of 32; ldx, ldy multiples of 8.
+ * Two kernels serve this call.  When w_hat/scale are requested and M, N are
+ * multiples of 256 and K of 64, one persistent launch samples every block once
+ * (all workgroups together), meets at a device-wide arrival barrier kept in a few
+ * device words of the library, and runs the GEMM on w_hat; two such calls must
+ * not run concurrently on one GPU.  Otherwise the sampling sits in the weight
+ * operand load of every output tile (no w_hat round trip, each block resampled
+ * per tile row).  Both give bit-identical w_hat and Y.                          */
 /* Plain BF16 GEMM with the same tiling as gws_linear_fwd and no sampling:
  * Y = X * W (or X * W^T when w_is_nk).  The reference point the fused kernel's
  * overhead is measured against.  w is device BF16 with leading dimension ldw.     */
