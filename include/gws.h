@@ -4,9 +4,8 @@
  * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
  * every other pointer is host memory.  The library allocates no device memory,
  * keeps no global state (one exception is stated at gws_linear_fwd) and is
- * thread-safe.  All GPU work is enqueued
- * asynchronously on the given stream (a hipStream_t passed as void*, NULL = the
- * default stream); no call synchronises.  The return value is a gws_status and
+ * thread-safe.  All GPU work is enqueued asynchronously on the given stream (a
+ * hipStream_t passed as void*, NULL = the default stream); no call synchronises.  The return value is a gws_status and
  * reports argument and launch errors only; on any error nothing has been
  * launched for the failing call.
  *
@@ -117,6 +116,10 @@ int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream);
  * not run concurrently on one GPU.  Otherwise the sampling sits in the weight
  * operand load of every output tile (no w_hat round trip, each block resampled
  * per tile row).  Both give bit-identical w_hat and Y.                          */
+int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
+                   const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
+                   void* y, int64_t ldy, void* stream);
+
 /* Plain BF16 GEMM with the same tiling as gws_linear_fwd and no sampling:
  * Y = X * W (or X * W^T when w_is_nk).  The reference point the fused kernel's
  * overhead is measured against.  w is device BF16 with leading dimension ldw.     */
