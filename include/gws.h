@@ -5,9 +5,9 @@
  * every other pointer is host memory.  The library allocates no device memory,
  * keeps no global state (one exception is stated at gws_linear_fwd) and is
  * thread-safe.  All GPU work is enqueued asynchronously on the given stream (a
- * hipStream_t passed as void*, NULL = the default stream); no call synchronises.  The return value is a gws_status and
- * reports argument and launch errors only; on any error nothing has been
- * launched for the failing call.
+ * hipStream_t passed as void*, NULL = the default stream); no call synchronises.
+ * The return value is a gws_status and reports argument and launch errors only;
+ * on any error nothing has been launched for the failing call.
  *
  * Notation follows the paper: w is a BF16 weight matrix [rows x cols], split in
  * square blocks of b_l = 32; b_t is the per-block bitwidth; R is the noise basis
