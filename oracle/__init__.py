@@ -72,6 +72,10 @@ def configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.gwso_sample_bwd.restype = ci
     L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
     L.gwso_linear_fwd.restype = ci
+    L.gwso_bitwidth.argtypes = [vp, i64, ctypes.c_float, ctypes.c_float, vp]
+    L.gwso_bitwidth.restype = None
+    L.gwso_bitwidth_grad.argtypes = [vp, vp, i64, ctypes.c_float, ctypes.c_float, ctypes.c_double, i64, vp]
+    L.gwso_bitwidth_grad.restype = None
     return L
 
 
@@ -199,6 +203,24 @@ def sample_bwd(g: np.ndarray, scale: np.ndarray, seed: int, step: int, cols: int
     if rc:
         raise RuntimeError(f"gwso_sample_bwd status {rc}")
     return dw, dbt, asum
+
+
+def bitwidth(bi: np.ndarray, b_init: float, b_target: float) -> np.ndarray:
+    """Eq. 11 in fp32: b_t = b_target + b_i * (b_init - b_target)."""
+    bi = np.ascontiguousarray(bi, dtype=np.float32)
+    bt = np.empty_like(bi)
+    lib().gwso_bitwidth(_ptr(bi), bi.size, b_init, b_target, _ptr(bt))
+    return bt
+
+
+def bitwidth_grad(bi: np.ndarray, dbt: np.ndarray, b_init: float, b_target: float, lam: float, m: int) -> np.ndarray:
+    """dL'/db_i of Eq. 12 (fp64) for blocks of a layer of m blocks, from dL/db_t."""
+    bi = np.ascontiguousarray(bi, dtype=np.float32)
+    dbt = np.ascontiguousarray(dbt, dtype=np.float64)
+    assert bi.shape == dbt.shape
+    dbi = np.empty_like(dbt)
+    lib().gwso_bitwidth_grad(_ptr(bi), _ptr(dbt), bi.size, b_init, b_target, lam, m, _ptr(dbi))
+    return dbi
 
 
 def linear_fwd(x: np.ndarray, q: np.ndarray, w_is_nk: bool = False, rows_sel=None):

@@ -19,7 +19,8 @@
  * exhaustive 2^16 enumeration of the bit->R map against Eq. 10's closed form,
  * torch CPU bfloat16 adds, torch CPU float8_e4m3fn casts, brute-force nearest
  * search over the enumerated FP6-E3M2 / FP8-E4M3 code sets, hand-worked
- * blocks, Table C.1, finite differences of Eq. 3 for Eq. 4.
+ * blocks, Table C.1, finite differences of Eq. 3 for Eq. 4, the end points
+ * of Eq. 11 and finite differences of Eq. 12.
  * Nothing here is "parity unpinned".
  */
 #include <math.h>
@@ -405,6 +406,37 @@ int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
     }
   }
   return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Bitwidth parametrisation (Sec. 3.6 "Bitwidth", Eq. 11 and Eq. 12).   */
+/*   b_t = b_target + b_i * (b_init - b_target), per block, in fp32:    */
+/*   the difference, the product and the sum are each rounded once, in  */
+/*   the order the equation is written.                                 */
+/* ------------------------------------------------------------------ */
+void gwso_bitwidth(const float* bi, int64_t n, float b_init, float b_target, float* bt) {
+  float delta = b_init - b_target;
+  for (int64_t k = 0; k < n; ++k) {
+    float prod = bi[k] * delta;
+    bt[k] = b_target + prod;
+  }
+}
+
+/* Gradient of L' = L + lambda * sum_layers( sum_blocks |b_t - b_target| / m )  */
+/* (Eq. 12) with respect to b_i, for the n blocks handed in, which belong to a  */
+/* layer of m blocks:                                                           */
+/*   dL'/db_i = (b_init - b_target) * ( dL/db_t + (lambda / m) * sgn(b_t - b_target) ) */
+/* sgn is taken on the fp32 b_t the forward pass used (sgn(0) = 0); everything  */
+/* else is fp64.                                                                */
+void gwso_bitwidth_grad(const float* bi, const double* dbt, int64_t n, float b_init,
+                        float b_target, double lambda, int64_t m, double* dbi) {
+  float delta = b_init - b_target;
+  for (int64_t k = 0; k < n; ++k) {
+    float prod = bi[k] * delta;
+    float bt = b_target + prod;
+    double sgn = bt > b_target ? 1.0 : (bt < b_target ? -1.0 : 0.0);
+    dbi[k] = (double)delta * (dbt[k] + lambda / (double)m * sgn);
+  }
 }
 
 /* ------------------------------------------------------------------ */

@@ -12,6 +12,7 @@ import pytest
 
 import oracle
 import test_oracle_arith as arith
+import test_oracle_bitwidth as bw
 import test_oracle_rng as rng
 import test_oracle_sample as smp
 
@@ -88,6 +89,21 @@ MUTANTS = [
      [smp.test_linear_vs_numpy_fp64_matmul]),
     ("linear: rounding of Y truncates", "if (rem > half || (rem == half && (keep & 1))) keep += 1;\n  int ef", "int ef",
      [smp.test_linear_vs_numpy_fp64_matmul]),
+    ("Eq. 11: offset is b_init instead of b_target", "bt[k] = b_target + prod;", "bt[k] = b_init + prod;",
+     [bw.test_eq11_end_points_and_midpoint]),
+    ("Eq. 11: slope sign", "float delta = b_init - b_target;\n  for (int64_t k = 0; k < n; ++k) {\n    float prod = bi[k] * delta;\n    bt[k]",
+     "float delta = b_target - b_init;\n  for (int64_t k = 0; k < n; ++k) {\n    float prod = bi[k] * delta;\n    bt[k]",
+     [bw.test_eq11_end_points_and_midpoint]),
+    ("Eq. 12: chain-rule factor dropped", "dbi[k] = (double)delta * (dbt[k]", "dbi[k] = (dbt[k]",
+     [bw.test_eq12_gradient_matches_finite_differences]),
+    ("Eq. 12: loss term not divided by the layer's block count", "lambda / (double)m * sgn", "lambda * sgn",
+     [bw.test_eq12_gradient_matches_finite_differences]),
+    ("Eq. 12: divided by the blocks handed in instead of the layer's", "lambda / (double)m * sgn", "lambda / (double)n * sgn",
+     [bw.test_eq12_gradient_matches_finite_differences]),
+    ("Eq. 12: sign of the loss term", "double sgn = bt > b_target ? 1.0", "double sgn = bt > b_target ? -1.0",
+     [bw.test_eq12_special_cases]),
+    ("Eq. 12: subgradient at zero not zero", "(bt < b_target ? -1.0 : 0.0)", "-1.0",
+     [bw.test_eq12_special_cases]),
 ]
 
 
