@@ -99,6 +99,33 @@ int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* str
  * call left it.  Uses fields g, dw, dbt, scale, rows, cols, ld, row0, col0, seed. */
 int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream);
 
+/* Bitwidth parametrisation of the paper's Sec. 3.6 "Bitwidth": every block keeps
+ * an internal parameter b_i (initialised to 1) and
+ *   b_t = b_target + b_i * (b_init - b_target)                          (Eq. 11)
+ * and the training loss may carry the term
+ *   lambda * sum_layers( sum_blocks |b_t - b_target| / m )              (Eq. 12)
+ * with m the number of blocks of the layer.  One gws_bitwidth per tensor (host).   */
+typedef struct gws_bitwidth {
+  float b_init;          /* bitwidth at b_i = 1                                     */
+  float b_target;        /* bitwidth at b_i = 0                                     */
+  float lambda;          /* weight of the loss term of Eq. 12; 0 = no such term     */
+  int64_t layer_blocks;  /* m of Eq. 12: blocks of the whole layer this tensor is, or
+                            is a shard of; 0 = the tensor's own block count         */
+} gws_bitwidth;
+
+/* gws_sample_fwd with the bitwidth given through b_i: the field `bt` of every
+ * descriptor holds b_i (device, fp32 per block) and the block uses
+ *   b_t = fl( b_target + fl( b_i * fl(b_init - b_target) ) )            (fp32)
+ * Everything else is gws_sample_fwd.  bw is a host array of n.                     */
+int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fmt, uint64_t step,
+                      void* stream);
+
+/* gws_sample_bwd for the parametrised bitwidth: writes, into the field `dbt`,
+ *   dL'/db_i = (b_init - b_target) * ( dL/db_t + lambda / m * sgn(b_t - b_target) )
+ * with dL/db_t as in gws_sample_bwd, b_t recomputed from b_i (field `bt`, required
+ * here) as the forward call formed it, and sgn(0) = 0.  fp32.                       */
+int gws_sample_bwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, uint64_t step, void* stream);
+
 /* Fused sampled-weight linear: Y = X * w_hat with w_hat produced as in
  * gws_sample_fwd inside the GEMM kernel (the paper, Sec. 3.5 "Separate kernels",
  * keeps sampling and matmul apart; this is the fused alternative).

@@ -16,8 +16,8 @@ _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 
-EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_linear_fwd", "gws_gemm_bf16", "gws_noise_packed",
-           "gws_derive_seed", "gws_status_string", "gws_version")
+EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_linear_fwd",
+           "gws_gemm_bf16", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
 
 
 class GwsError(RuntimeError):
@@ -32,6 +32,20 @@ class _CTensor(ctypes.Structure):
                 ("dbt", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
                 ("ld", ctypes.c_int64), ("row0", ctypes.c_int64), ("col0", ctypes.c_int64),
                 ("seed", ctypes.c_uint64)]
+
+
+class _CBitwidth(ctypes.Structure):
+    _fields_ = [("b_init", ctypes.c_float), ("b_target", ctypes.c_float), ("lam", ctypes.c_float),
+                ("layer_blocks", ctypes.c_int64)]
+
+
+@dataclass
+class Bitwidth:
+    """Python-side mirror of ``gws_bitwidth`` (paper Eq. 11 and Eq. 12), one per tensor."""
+    b_init: float
+    b_target: float
+    lam: float = 0.0
+    layer_blocks: int = 0
 
 
 @dataclass
@@ -75,6 +89,11 @@ def load_library() -> ctypes.CDLL:
     L.gws_sample_fwd.restype = ci
     L.gws_sample_bwd.argtypes = [tp, ci, u64, vp]
     L.gws_sample_bwd.restype = ci
+    bp = ctypes.POINTER(_CBitwidth)
+    L.gws_sample_fwd_bi.argtypes = [tp, ci, bp, ci, u64, vp]
+    L.gws_sample_fwd_bi.restype = ci
+    L.gws_sample_bwd_bi.argtypes = [tp, ci, bp, u64, vp]
+    L.gws_sample_bwd_bi.restype = ci
     L.gws_linear_fwd.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
     L.gws_linear_fwd.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
@@ -165,6 +184,44 @@ def gws_sample_bwd(t: Sequence[TensorDesc], step: int, stream=None) -> None:
     L = load_library()
     arr, n = _as_c(t)
     _check(L.gws_sample_bwd(arr, n, int(step), _stream(stream)), "gws_sample_bwd")
+
+
+class PackedBitwidth:
+    """Bitwidth settings already marshalled into a C array of ``gws_bitwidth`` (see :func:`pack_bitwidth`)."""
+
+    def __init__(self, arr, n):
+        self.arr, self.n = arr, n
+
+    def __len__(self):
+        return self.n
+
+
+def pack_bitwidth(bw: Sequence[Bitwidth]) -> PackedBitwidth:
+    arr = (_CBitwidth * max(1, len(bw)))()
+    for c, b in zip(arr, bw):
+        c.b_init, c.b_target, c.lam, c.layer_blocks = b.b_init, b.b_target, b.lam, b.layer_blocks
+    return PackedBitwidth(arr, len(bw))
+
+
+def _marshal_bw(bw, n: int):
+    if len(bw) != n:
+        raise ValueError(f"{n} tensors but {len(bw)} bitwidth settings")
+    return (bw if isinstance(bw, PackedBitwidth) else pack_bitwidth(bw)).arr
+
+
+def gws_sample_fwd_bi(t: Sequence[TensorDesc], bw: Sequence[Bitwidth], fmt: int, step: int, stream=None) -> None:
+    """``gws_sample_fwd`` with ``bt`` holding the internal parameter b_i of paper Eq. 11."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_fwd_bi(arr, n, _marshal_bw(bw, n), int(fmt), int(step), _stream(stream)),
+           "gws_sample_fwd_bi")
+
+
+def gws_sample_bwd_bi(t: Sequence[TensorDesc], bw: Sequence[Bitwidth], step: int, stream=None) -> None:
+    """``gws_sample_bwd`` writing dL'/db_i (paper Eq. 11, Eq. 12) into ``dbt``; needs ``bt`` = b_i."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_bwd_bi(arr, n, _marshal_bw(bw, n), int(step), _stream(stream)), "gws_sample_bwd_bi")
 
 
 def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:

@@ -63,7 +63,9 @@ inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
 
 // Pack descriptors into as few launches as the kernel-argument segment and the
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
-int run_batched(const gws_tensor* t, int n, bool fwd, int fmt, uint64_t step, hipStream_t stream) {
+// `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
+int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, bool fwd, int fmt, uint64_t step,
+                hipStream_t stream) {
   // Block rows per workgroup.  Forward: 1 (most workgroups, fewest registers).  Backward
   // does less per tile, so a workgroup takes up to 8 while at least ~20 workgroups per
   // compute unit remain to balance the 256 units.
@@ -105,6 +107,20 @@ int run_batched(const gws_tensor* t, int n, bool fwd, int fmt, uint64_t step, hi
       d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
     }
     fill_common(d, t[i]);
+    d.p4 = nullptr;
+    d.b_target = 0.0f;
+    d.b_delta = 1.0f;
+    d.lambda_m = 0.0f;
+    if (bw) {
+      d.b_target = bw[i].b_target;
+      d.b_delta = bw[i].b_init - bw[i].b_target;
+      if (!fwd) {
+        const int64_t own = ((t[i].rows + 31) / 32) * ((t[i].cols + 31) / 32);
+        const int64_t m = bw[i].layer_blocks > 0 ? bw[i].layer_blocks : own;
+        d.p4 = t[i].bt;
+        d.lambda_m = bw[i].lambda / (float)m;
+      }
+    }
     wgs += wc;
   }
   return flush();
@@ -123,7 +139,7 @@ int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* str
     int rc = check_fwd(t[i]);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(t, n, true, fmt, step, (hipStream_t)stream);
+  return run_batched(t, n, nullptr, true, fmt, step, (hipStream_t)stream);
 }
 
 int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
@@ -134,7 +150,34 @@ int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
     int rc = check_bwd(t[i]);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(t, n, false, 0, step, (hipStream_t)stream);
+  return run_batched(t, n, nullptr, false, 0, step, (hipStream_t)stream);
+}
+
+int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fmt, uint64_t step, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t || !bw) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_fwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, bw, true, fmt, step, (hipStream_t)stream);
+}
+
+int gws_sample_bwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, uint64_t step, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t || !bw) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_bwd(t[i]);
+    if (rc != GWS_OK) return rc;
+    if (bw[i].layer_blocks < 0) return GWS_ERR_SHAPE;
+    if (t[i].rows == 0 || t[i].cols == 0) continue;
+    if (!t[i].bt) return GWS_ERR_NULL;
+    if (!aligned(t[i].bt, 4)) return GWS_ERR_ALIGN;
+  }
+  return run_batched(t, n, bw, false, 0, step, (hipStream_t)stream);
 }
 
 int gws_noise_packed(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0,
@@ -222,6 +265,6 @@ const char* gws_status_string(int status) {
   }
 }
 
-int gws_version(void) { return 1; }
+int gws_version(void) { return 2; }
 
 }  // extern "C"

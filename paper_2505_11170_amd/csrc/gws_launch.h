@@ -14,19 +14,30 @@ constexpr int kTileCols = 256;      // a workgroup covers 32 rows x 256 columns
 constexpr int kMaxTensorsPerLaunch = 56;
 
 // One tensor as a kernel sees it.  p0..p3 are, for the forward pass,
-// (w, w_hat, bt, scale) and, for the backward pass, (g, dw-or-NULL, dbt, scale).
+// (w, w_hat, bt-or-b_i, scale) and, for the backward pass, (g, dw-or-NULL,
+// dbt-or-db_i, scale); p4 is the backward pass's b_i (NULL: the gradient asked
+// for is dL/db_t itself).
+// The bitwidth a block uses is b_t = b_target + v * b_delta (paper Eq. 11) with v
+// the value read through p2; a plain b_t input is the case b_target = 0,
+// b_delta = 1, which leaves every finite value as it is.
 struct TileDesc {
   const void* p0;
   void* p1;
   void* p2;
   void* p3;
+  const float* p4;
   uint32_t rows, cols, ld;
   uint32_t row0, cg0;          // shard origin: row offset, column-group (col0 / 8) offset
   uint32_t seed_lo, seed_hi;
   uint32_t tiles_x;            // workgroup tiles per block row = ceil(cols / 256)
+  float b_target, b_delta;     // Eq. 11: b_delta = b_init - b_target
+  float lambda_m;              // Eq. 12: lambda / (blocks of the layer); backward only
+  uint32_t reserved;
 };
+static_assert(sizeof(TileDesc) == 88, "descriptor layout");
 
-// Passed by value: lives in the kernel-argument segment (at most 4 KiB).
+// Passed by value: lives in the kernel-argument segment (about 5 KiB; the segment
+// of a gfx950 code object is not limited to 4 KiB).
 struct LaunchArgs {
   // First workgroup of every tensor within the launch; entries past n hold 0x7FFFFFFF.
   // Kept apart from the descriptors so a wavefront reads the whole prefix with a few
@@ -37,7 +48,7 @@ struct LaunchArgs {
   uint32_t step_lo, step_hi;
   uint32_t tiles_per_wg;       // consecutive block rows one workgroup walks down (>= 1)
 };
-static_assert(sizeof(LaunchArgs) <= 3968, "kernel arguments must fit the 4 KiB segment");
+static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the size verified on the device");
 
 int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, hipStream_t stream);
 int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);

@@ -97,9 +97,18 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   const uint32_t nbc = (d.cols + 31) >> 5;
   const uint32_t bcol = (col_base >> 5) + (gc >> 2);
   if ((FULL || bcol < nbc) && (gc & 3) == 0 && r0 == 0) {
-    const float s32 = scale[(size_t)by * nbc + bcol];
+    const size_t blk = (size_t)by * nbc + bcol;
+    const float s32 = scale[blk];
     const float neg_ln2 = __uint_as_float(0xBF317218u);  // -ln 2
-    dbt[(size_t)by * nbc + bcol] = (neg_ln2 * s32) * acc;
+    float grad = (neg_ln2 * s32) * acc;                  // dL/db_t, Eq. 4
+    if (d.p4 != nullptr) {
+      // dL'/db_i, Eq. 11 and Eq. 12: b_t is recomputed exactly as the forward pass formed it,
+      // the subgradient of |b_t - b_target| at 0 is taken as 0
+      const float btv = __fadd_rn(d.b_target, __fmul_rn(d.p4[blk], d.b_delta));
+      const float sgn = btv > d.b_target ? 1.0f : (btv < d.b_target ? -1.0f : 0.0f);
+      grad = d.b_delta * (grad + d.lambda_m * sgn);
+    }
+    dbt[blk] = grad;
   }
 }
 

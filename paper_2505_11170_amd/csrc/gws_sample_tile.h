@@ -96,7 +96,9 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   const uint32_t nbc = (d.cols + 31) >> 5;
   const uint32_t bcol = (col_base >> 5) + (gc >> 2);
   const bool block_exists = FULL || bcol < nbc;
-  const float btv = block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f;
+  const float bv = block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f;
+  // Eq. 11 (the product and the sum rounded separately); identity for a plain b_t
+  const float btv = __fadd_rn(d.b_target, __fmul_rn(bv, d.b_delta));
   BlockScale b = block_scale(a16, btv);
   if (FMT == 1) cast_constants<8, -6>(a16, b);
   if (FMT == 2) cast_constants<4, -2>(a16, b);
