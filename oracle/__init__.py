@@ -72,6 +72,12 @@ def configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.gwso_sample_bwd.restype = ci
     L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
     L.gwso_linear_fwd.restype = ci
+    L.gwso_mx_code_value.argtypes = [ci, ci]
+    L.gwso_mx_code_value.restype = ctypes.c_double
+    L.gwso_mx_encode.argtypes = [ctypes.c_uint16, ci, ci]
+    L.gwso_mx_encode.restype = ci
+    L.gwso_sample_fwd_mx.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, u64, u64, vp, i64, vp, vp]
+    L.gwso_sample_fwd_mx.restype = ci
     L.gwso_bitwidth.argtypes = [vp, i64, ctypes.c_float, ctypes.c_float, vp]
     L.gwso_bitwidth.restype = None
     L.gwso_bitwidth_grad.argtypes = [vp, vp, i64, ctypes.c_float, ctypes.c_float, ctypes.c_double, i64, vp]
@@ -203,6 +209,38 @@ def sample_bwd(g: np.ndarray, scale: np.ndarray, seed: int, step: int, cols: int
     if rc:
         raise RuntimeError(f"gwso_sample_bwd status {rc}")
     return dw, dbt, asum
+
+
+def mx_code_value(code: int, fmt: int) -> float:
+    return float(lib().gwso_mx_code_value(code, fmt))
+
+
+def mx_encode(q16: int, Ea: int, fmt: int) -> int:
+    return int(lib().gwso_mx_encode(q16, Ea, fmt))
+
+
+def mx_row_bytes(cols: int, fmt: int) -> int:
+    return cols if fmt == FMT_FP8_E4M3 else (cols * 6 + 7) // 8
+
+
+def sample_fwd_mx(w: np.ndarray, bt: np.ndarray, fmt: int, seed: int, step: int, cols: int | None = None,
+                  row0: int = 0, col0: int = 0, ldc: int | None = None):
+    """Forward pass with MX output.  Returns (codes uint8 [rows, ldc], xscale uint8 [nbr, nbc], scale float32).
+    Bytes of `codes` past a row's data keep the fill value 0xAA."""
+    assert w.dtype == np.uint16 and w.ndim == 2 and w.flags.c_contiguous
+    rows, ld = w.shape
+    cols = ld if cols is None else cols
+    nbr, nbc = n_blocks(rows, cols)
+    bt = np.ascontiguousarray(bt, dtype=np.float32).reshape(nbr, nbc)
+    ldc = mx_row_bytes(cols, fmt) if ldc is None else ldc
+    codes = np.full((rows, ldc), 0xAA, dtype=np.uint8)
+    xscale = np.zeros((nbr, nbc), dtype=np.uint8)
+    scale = np.empty((nbr, nbc), dtype=np.float32)
+    rc = lib().gwso_sample_fwd_mx(_ptr(w), rows, cols, ld, row0, col0, _ptr(bt), fmt, seed, step, _ptr(codes), ldc,
+                                  _ptr(xscale), _ptr(scale))
+    if rc:
+        raise RuntimeError(f"gwso_sample_fwd_mx status {rc}")
+    return codes, xscale, scale
 
 
 def bitwidth(bi: np.ndarray, b_init: float, b_target: float) -> np.ndarray:

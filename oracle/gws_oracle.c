@@ -20,7 +20,9 @@
  * torch CPU bfloat16 adds, torch CPU float8_e4m3fn casts, brute-force nearest
  * search over the enumerated FP6-E3M2 / FP8-E4M3 code sets, hand-worked
  * blocks, Table C.1, finite differences of Eq. 3 for Eq. 4, the end points
- * of Eq. 11 and finite differences of Eq. 12.
+ * of Eq. 11 and finite differences of Eq. 12; for the MX output torch's
+ * float8 byte patterns, the element-format figures of the OCP Microscaling
+ * specification, numpy's bit unpacking and the BF16-container output itself.
  * Nothing here is "parity unpinned".
  */
 #include <math.h>
@@ -405,6 +407,103 @@ int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
       if (abs_sum) abs_sum[bi * nbc + bj] = ln2 * s * aacc;
     }
   }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* The sampled weight as microscaling (MX) data: the deployment format  */
+/* the paper targets (Sec. 3.1: MXFP; square blocks, so W and its        */
+/* transpose share the bytes).  Per 32x32 block one E8M0 scale byte,     */
+/* the biased exponent of X = 2^(Ea + 1 - emax), and per element the     */
+/* code of q / X in the element format (OCP MX: FP8 E4M3, bias 7, no     */
+/* Inf, S.1111.111 = NaN never produced; FP6 E3M2, bias 3, no NaN/Inf).  */
+/* q is the value gwso_sample_fwd stores in its BF16 container.          */
+/* ------------------------------------------------------------------ */
+
+/* Value of an element code, by the format's definition. */
+double gwso_mx_code_value(int code, int fmt) {
+  int emax, emin, m;
+  double maxv;
+  fmt_params(fmt, &emax, &emin, &m, &maxv);
+  int ebits = (fmt == GWSO_FMT_FP8_E4M3) ? 4 : 3;
+  int mant = code & ((1 << m) - 1);
+  int E = (code >> m) & ((1 << ebits) - 1);
+  int sign = (code >> (m + ebits)) & 1;
+  int bias = 1 - emin;
+  double mag = E == 0 ? ldexp((double)mant, emin - m)
+                      : ldexp(1.0 + (double)mant / (double)(1 << m), E - bias);
+  return sign ? -mag : mag;
+}
+
+/* Code of a BF16 value that is a member of X * format: found by running
+ * through the format's codes (0xFF if the value is not a member). */
+int gwso_mx_encode(uint16_t q16, int Ea, int fmt) {
+  int emax, emin, m;
+  double maxv;
+  fmt_params(fmt, &emax, &emin, &m, &maxv);
+  int ebits = (fmt == GWSO_FMT_FP8_E4M3) ? 4 : 3;
+  int nmag = 1 << (m + ebits);
+  double y = fabs(ldexp((double)bf16_to_f32(q16), -(Ea + 1 - emax)));
+  for (int c = 0; c < nmag; ++c) {
+    if (fmt == GWSO_FMT_FP8_E4M3 && c == 0x7F) continue; /* NaN */
+    if (gwso_mx_code_value(c, fmt) == y) return c | ((q16 & 0x8000u) ? nmag : 0);
+  }
+  return 0xFF;
+}
+
+/* Forward pass with MX output.
+ *   codes  : FP8: one byte per element, row stride ldc bytes.
+ *            FP6: element j of a row occupies bits [6j, 6j+6) of the row's
+ *            bytes read as a little-endian bit string (8 elements = 6 bytes);
+ *            unused bits of the last byte touched are 0.
+ *   xscale : [nbr x nbc] bytes, Ea + 1 - emax + 127 (127 for an all-zero block)
+ *   scale  : s32 as in gwso_sample_fwd                                        */
+int gwso_sample_fwd_mx(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
+                       int64_t row0, int64_t col0, const float* bt, int fmt,
+                       uint64_t seed, uint64_t step, uint8_t* codes, int64_t ldc,
+                       uint8_t* xscale, float* scale) {
+  if (!w || !bt || !codes || !xscale || !scale) return 1;
+  if (fmt != GWSO_FMT_FP8_E4M3 && fmt != GWSO_FMT_FP6_E3M2) return 4;
+  uint16_t* q = (uint16_t*)malloc((size_t)(rows > 0 ? rows : 1) * (size_t)ld * sizeof(uint16_t));
+  if (!q) return 5;
+  int rc = gwso_sample_fwd(w, rows, cols, ld, row0, col0, bt, fmt, seed, step, q, scale);
+  if (rc) { free(q); return rc; }
+  int emax, emin, m;
+  double maxv;
+  fmt_params(fmt, &emax, &emin, &m, &maxv);
+  int64_t nbr = (rows + GWSO_BL - 1) / GWSO_BL, nbc = (cols + GWSO_BL - 1) / GWSO_BL;
+  /* block scales: Ea = floor(log2 max|w|) from the block maximum, the plain way */
+  for (int64_t bi = 0; bi < nbr; ++bi)
+    for (int64_t bj = 0; bj < nbc; ++bj) {
+      int64_t i0 = bi * GWSO_BL, j0 = bj * GWSO_BL;
+      int64_t i1 = i0 + GWSO_BL < rows ? i0 + GWSO_BL : rows;
+      int64_t j1 = j0 + GWSO_BL < cols ? j0 + GWSO_BL : cols;
+      uint16_t a16 = 0;
+      for (int64_t i = i0; i < i1; ++i)
+        for (int64_t j = j0; j < j1; ++j) {
+          uint16_t mag = w[i * ld + j] & 0x7FFFu;
+          if (mag > a16) a16 = mag;
+        }
+      int Ea = a16 ? floor_log2_bf16(a16) : emax - 1;   /* all-zero block: X = 1 */
+      xscale[bi * nbc + bj] = (uint8_t)(Ea + 1 - emax + 127);
+    }
+  int64_t row_bytes = fmt == GWSO_FMT_FP8_E4M3 ? cols : (cols * 6 + 7) / 8;
+  for (int64_t i = 0; i < rows; ++i) {
+    memset(codes + i * ldc, 0, (size_t)row_bytes);
+    for (int64_t j = 0; j < cols; ++j) {
+      int Ea = (int)xscale[(i / GWSO_BL) * nbc + j / GWSO_BL] - 127 - 1 + emax;
+      int code = gwso_mx_encode(q[i * ld + j], Ea, fmt);
+      if (fmt == GWSO_FMT_FP8_E4M3) {
+        codes[i * ldc + j] = (uint8_t)code;
+      } else {
+        for (int b = 0; b < 6; ++b) {
+          int64_t bit = 6 * j + b;
+          if ((code >> b) & 1) codes[i * ldc + bit / 8] |= (uint8_t)(1u << (bit % 8));
+        }
+      }
+    }
+  }
+  free(q);
   return 0;
 }
 

@@ -13,6 +13,7 @@ import pytest
 import oracle
 import test_oracle_arith as arith
 import test_oracle_bitwidth as bw
+import test_oracle_mx as mx
 import test_oracle_rng as rng
 import test_oracle_sample as smp
 
@@ -104,6 +105,22 @@ MUTANTS = [
      [bw.test_eq12_special_cases]),
     ("Eq. 12: subgradient at zero not zero", "(bt < b_target ? -1.0 : 0.0)", "-1.0",
      [bw.test_eq12_special_cases]),
+    ("MX: shared exponent biased by 128", "xscale[bi * nbc + bj] = (uint8_t)(Ea + 1 - emax + 127);",
+     "xscale[bi * nbc + bj] = (uint8_t)(Ea + 1 - emax + 128);", [mx.test_hand_block_scales]),
+    ("MX: shared exponent without the headroom binade", "xscale[bi * nbc + bj] = (uint8_t)(Ea + 1 - emax + 127);",
+     "xscale[bi * nbc + bj] = (uint8_t)(Ea - emax + 127);", [mx.test_hand_block_scales]),
+    ("MX: all-zero block does not get X = 1", "floor_log2_bf16(a16) : emax - 1;", "floor_log2_bf16(a16) : 0;",
+     [mx.test_hand_block_scales]),
+    ("MX: FP6 fields packed from the top bit of each byte", "(uint8_t)(1u << (bit % 8))", "(uint8_t)(0x80u >> (bit % 8))",
+     [lambda: mx.test_mx_output_decodes_to_the_bf16_container_output(oracle.FMT_FP6_E3M2, (40, 50))]),
+    ("MX: FP6 field written top bit first", "int64_t bit = 6 * j + b;", "int64_t bit = 6 * j + (5 - b);",
+     [lambda: mx.test_mx_output_decodes_to_the_bf16_container_output(oracle.FMT_FP6_E3M2, (40, 50))]),
+    ("MX: exponent bias off by one", "int bias = 1 - emin;", "int bias = -emin;",
+     [mx.test_e3m2_code_values_match_the_specification_figures, mx.test_e4m3_code_values_match_torch_float8]),
+    ("MX: subnormal codes scaled like normals", "ldexp((double)mant, emin - m)", "ldexp((double)mant, emin - m - 1)",
+     [mx.test_e3m2_code_values_match_the_specification_figures]),
+    ("MX: sign bit one position low", "? nmag : 0);", "? (nmag >> 1) : 0);",
+     [lambda: mx.test_encode_inverts_the_code_values_at_any_block_scale(oracle.FMT_FP8_E4M3)]),
 ]
 
 
