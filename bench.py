@@ -243,6 +243,10 @@ def main():
         except Exception as e:  # pragma: no cover
             extras["parametrised_bitwidth_error"] = repr(e)
         try:
+            extras["mx_output"] = mx_bench(torch, gws, synth, dev, shapes, params)
+        except Exception as e:  # pragma: no cover
+            extras["mx_output_error"] = repr(e)
+        try:
             extras["copy_ceiling"] = copy_ceiling(torch)
             extras["fused_linear"] = linear_bench(torch, gws, synth, dev)
         except Exception as e:  # pragma: no cover
@@ -270,6 +274,38 @@ def _time_ms(torch, fn, iters, warmup=3):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def mx_bench(torch, gws, synth, dev, shapes, params):
+    """Forward pass writing MX element codes + E8M0 block scales instead of the BF16 container."""
+    out = {}
+    blocks = sum(synth.n_blocks(s.rows, s.cols)[0] * synth.n_blocks(s.rows, s.cols)[1] for s in shapes)
+    for name, fmt, bpp in (("fp8_e4m3", gws.FMT_FP8_E4M3, 1.0), ("fp6_e3m2", gws.FMT_FP6_E3M2, 0.75)):
+        sets = []
+        for k in range(3):      # rotate three buffer sets, as the main measurement does
+            descs, outs = [], []
+            for i, sh in enumerate(shapes):
+                t = synth.make_tensor(100 * k + i, sh.rows, sh.cols, device=dev, with_grad=False)
+                nbr, nbc = synth.n_blocks(sh.rows, sh.cols)
+                ldc = sh.cols if fmt == gws.FMT_FP8_E4M3 else sh.cols * 6 // 8
+                descs.append(gws.TensorDesc(rows=sh.rows, cols=sh.cols, seed=gws.gws_derive_seed(0, i), w=t["w"],
+                                            bt=t["bt"], scale=torch.empty(nbr, nbc, device=dev)))
+                outs.append(gws.MxOut(torch.empty(sh.rows, ldc, dtype=torch.uint8, device=dev),
+                                      torch.empty(nbr, nbc, dtype=torch.uint8, device=dev), ldc))
+            sets.append((gws.pack(descs), gws.pack_mx(outs)))
+        step = [0]
+
+        def fn():
+            p, o = sets[step[0] % 3]
+            gws.gws_sample_fwd_mx(p, o, fmt, step[0])
+            step[0] += 1
+        ms = _time_ms(torch, fn, 60, warmup=20)
+        nbytes = (2.0 + bpp) * params + 9.0 * blocks
+        out[name] = {"fwd_ms": ms, "params_per_s": params / ms * 1e3, "bytes_per_param": 2.0 + bpp,
+                     "GBps": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS}
+        del sets
+        torch.cuda.empty_cache()
+    return out
 
 
 def copy_ceiling(torch):

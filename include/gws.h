@@ -126,6 +126,30 @@ int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fm
  * here) as the forward call formed it, and sgn(0) = 0.  fp32.                       */
 int gws_sample_bwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, uint64_t step, void* stream);
 
+/* The sampled weight as microscaling (MX) data, the deployment form of the formats
+ * the paper targets (Sec. 3.1; with square blocks the same bytes serve W and its
+ * transpose): per 32x32 block one E8M0 byte, the biased exponent of the cast's scale
+ * X = 2^(xscale - 127), and per element the code of q / X in the element format,
+ * where q is the value gws_sample_fwd stores in its BF16 container:
+ *   q[i][j] == X(block of i, j) * value(code[i][j])      exactly.
+ * FP8-E4M3 (bias 7; the NaN pattern S.1111.111 is never produced): one byte per
+ * element, row i at codes + i * ldc.  FP6-E3M2 (bias 3): element j of row i occupies
+ * bits [6j, 6j + 6) of the bytes at codes + i * ldc read as a little-endian bit
+ * string (8 elements = 6 bytes; unused bits of a row's last byte are written as 0).
+ * An all-zero block gets xscale = 127.  Bytes past a row's data are never written.  */
+typedef struct gws_mx_out {
+  void* codes;      /* device; 8-byte aligned for FP8, 2-byte aligned for FP6            */
+  uint8_t* xscale;  /* device, [ceil(rows/32) x ceil(cols/32)] bytes                     */
+  int64_t ldc;      /* bytes per row of codes: >= cols and a multiple of 8 (FP8),
+                       >= ceil(cols * 6 / 8) and a multiple of 2 (FP6)                   */
+} gws_mx_out;
+
+/* gws_sample_fwd with MX output: for tensor i writes o[i].codes, o[i].xscale and
+ * t[i].scale (the backward pass needs it); t[i].w_hat is not used.  fmt is
+ * GWS_FMT_FP8_E4M3 or GWS_FMT_FP6_E3M2.  o is a host array of n.                      */
+int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, uint64_t step,
+                      void* stream);
+
 /* Fused sampled-weight linear: Y = X * w_hat with w_hat produced as in
  * gws_sample_fwd inside the GEMM kernel (the paper, Sec. 3.5 "Separate kernels",
  * keeps sampling and matmul apart; this is the fused alternative).

@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 
-EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_linear_fwd",
+EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd",
            "gws_gemm_bf16", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
 
 
@@ -37,6 +37,18 @@ class _CTensor(ctypes.Structure):
 class _CBitwidth(ctypes.Structure):
     _fields_ = [("b_init", ctypes.c_float), ("b_target", ctypes.c_float), ("lam", ctypes.c_float),
                 ("layer_blocks", ctypes.c_int64)]
+
+
+class _CMxOut(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("xscale", ctypes.c_void_p), ("ldc", ctypes.c_int64)]
+
+
+@dataclass
+class MxOut:
+    """Python-side mirror of ``gws_mx_out``: uint8 device tensors for element codes and E8M0 block scales."""
+    codes: object
+    xscale: object
+    ldc: Optional[int] = None
 
 
 @dataclass
@@ -94,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     L.gws_sample_fwd_bi.restype = ci
     L.gws_sample_bwd_bi.argtypes = [tp, ci, bp, u64, vp]
     L.gws_sample_bwd_bi.restype = ci
+    L.gws_sample_fwd_mx.argtypes = [tp, ctypes.POINTER(_CMxOut), ci, ci, u64, vp]
+    L.gws_sample_fwd_mx.restype = ci
     L.gws_linear_fwd.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
     L.gws_linear_fwd.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
@@ -222,6 +236,36 @@ def gws_sample_bwd_bi(t: Sequence[TensorDesc], bw: Sequence[Bitwidth], step: int
     L = load_library()
     arr, n = _as_c(t)
     _check(L.gws_sample_bwd_bi(arr, n, _marshal_bw(bw, n), int(step), _stream(stream)), "gws_sample_bwd_bi")
+
+
+class PackedMxOut:
+    """MX output descriptors already marshalled into a C array of ``gws_mx_out`` (see :func:`pack_mx`)."""
+
+    def __init__(self, arr, n, keepalive):
+        self.arr, self.n, self._keepalive = arr, n, keepalive
+
+    def __len__(self):
+        return self.n
+
+
+def pack_mx(outs: Sequence[MxOut]) -> PackedMxOut:
+    arr = (_CMxOut * max(1, len(outs)))()
+    for c, o in zip(arr, outs):
+        ldc = o.ldc
+        if ldc is None:
+            ldc = int(o.codes.stride(0)) if o.codes is not None and o.codes.dim() == 2 else 0
+        c.codes, c.xscale, c.ldc = _p(o.codes), _p(o.xscale), ldc
+    return PackedMxOut(arr, len(outs), list(outs))
+
+
+def gws_sample_fwd_mx(t: Sequence[TensorDesc], o: Sequence[MxOut], fmt: int, step: int, stream=None) -> None:
+    """``gws_sample_fwd`` writing MX element codes and E8M0 block scales instead of ``w_hat``."""
+    L = load_library()
+    arr, n = _as_c(t)
+    if len(o) != n:
+        raise ValueError(f"{n} tensors but {len(o)} MX outputs")
+    oa = (o if isinstance(o, PackedMxOut) else pack_mx(o)).arr
+    _check(L.gws_sample_fwd_mx(arr, oa, n, int(fmt), int(step), _stream(stream)), "gws_sample_fwd_mx")
 
 
 def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:

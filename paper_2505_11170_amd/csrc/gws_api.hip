@@ -35,6 +35,23 @@ int check_fwd(const gws_tensor& t) {
   return GWS_OK;
 }
 
+inline bool overlap2(const void* a, size_t abytes, const void* b, size_t bbytes) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + bbytes && y < x + abytes;
+}
+
+int check_fwd_mx(const gws_tensor& t, const gws_mx_out& o, int fmt) {
+  int rc = check_shape(t);
+  if (rc != GWS_OK || t.rows == 0 || t.cols == 0) return rc;
+  if (!t.w || !t.bt || !t.scale || !o.codes || !o.xscale) return GWS_ERR_NULL;
+  const bool fp8 = fmt == GWS_FMT_FP8_E4M3;
+  const int64_t row_bytes = fp8 ? t.cols : (t.cols * 6 + 7) / 8;
+  if (o.ldc < row_bytes || o.ldc >= (int64_t)1 << 31 || (o.ldc & (fp8 ? 7 : 1)) != 0) return GWS_ERR_SHAPE;
+  if (!aligned(t.w, 16) || !aligned(t.bt, 4) || !aligned(t.scale, 4) || !aligned(o.codes, fp8 ? 8 : 2)) return GWS_ERR_ALIGN;
+  if (overlap2(t.w, (size_t)t.rows * t.ld * 2, o.codes, (size_t)t.rows * o.ldc)) return GWS_ERR_ALIAS;
+  return GWS_OK;
+}
+
 int check_bwd(const gws_tensor& t) {
   int rc = check_shape(t);
   if (rc != GWS_OK || t.rows == 0 || t.cols == 0) return rc;
@@ -64,8 +81,9 @@ inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
 // Pack descriptors into as few launches as the kernel-argument segment and the
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 // `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
-int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, bool fwd, int fmt, uint64_t step,
-                hipStream_t stream) {
+// `mx` (one per tensor, forward only) switches the output to MX element codes and block scales.
+int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx_out* mx, bool fwd, int fmt,
+                uint64_t step, hipStream_t stream) {
   // Block rows per workgroup.  Forward: 1 (most workgroups, fewest registers).  Backward
   // does less per tile, so a workgroup takes up to 8 while at least ~20 workgroups per
   // compute unit remain to balance the 256 units.
@@ -85,7 +103,8 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, bool fwd, in
   uint64_t wgs = 0;
   auto flush = [&]() -> int {
     if (a.n == 0) return GWS_OK;
-    int rc = fwd ? launch_sample_fwd(a, (uint32_t)wgs, fmt, stream) : launch_sample_bwd(a, (uint32_t)wgs, stream);
+    int rc = fwd ? launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, stream)
+                 : launch_sample_bwd(a, (uint32_t)wgs, stream);
     a.n = 0;
     wgs = 0;
     for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
@@ -111,13 +130,19 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, bool fwd, in
     d.b_target = 0.0f;
     d.b_delta = 1.0f;
     d.lambda_m = 0.0f;
+    d.ldc = 0;
+    if (mx) {
+      d.p1 = mx[i].codes;
+      d.p4 = mx[i].xscale;
+      d.ldc = (uint32_t)mx[i].ldc;
+    }
     if (bw) {
       d.b_target = bw[i].b_target;
       d.b_delta = bw[i].b_init - bw[i].b_target;
       if (!fwd) {
         const int64_t own = ((t[i].rows + 31) / 32) * ((t[i].cols + 31) / 32);
         const int64_t m = bw[i].layer_blocks > 0 ? bw[i].layer_blocks : own;
-        d.p4 = t[i].bt;
+        d.p4 = (void*)t[i].bt;
         d.lambda_m = bw[i].lambda / (float)m;
       }
     }
@@ -139,7 +164,7 @@ int gws_sample_fwd(const gws_tensor* t, int n, int fmt, uint64_t step, void* str
     int rc = check_fwd(t[i]);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(t, n, nullptr, true, fmt, step, (hipStream_t)stream);
+  return run_batched(t, n, nullptr, nullptr, true, fmt, step, (hipStream_t)stream);
 }
 
 int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
@@ -150,7 +175,7 @@ int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
     int rc = check_bwd(t[i]);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(t, n, nullptr, false, 0, step, (hipStream_t)stream);
+  return run_batched(t, n, nullptr, nullptr, false, 0, step, (hipStream_t)stream);
 }
 
 int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fmt, uint64_t step, void* stream) {
@@ -162,7 +187,19 @@ int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fm
     int rc = check_fwd(t[i]);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(t, n, bw, true, fmt, step, (hipStream_t)stream);
+  return run_batched(t, n, bw, nullptr, true, fmt, step, (hipStream_t)stream);
+}
+
+int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, uint64_t step, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t || !o) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_fwd_mx(t[i], o[i], fmt);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, nullptr, o, true, fmt, step, (hipStream_t)stream);
 }
 
 int gws_sample_bwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, uint64_t step, void* stream) {
@@ -177,7 +214,7 @@ int gws_sample_bwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, uint64
     if (!t[i].bt) return GWS_ERR_NULL;
     if (!aligned(t[i].bt, 4)) return GWS_ERR_ALIGN;
   }
-  return run_batched(t, n, bw, false, 0, step, (hipStream_t)stream);
+  return run_batched(t, n, bw, nullptr, false, 0, step, (hipStream_t)stream);
 }
 
 int gws_noise_packed(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0,
@@ -265,6 +302,6 @@ const char* gws_status_string(int status) {
   }
 }
 
-int gws_version(void) { return 2; }
+int gws_version(void) { return 3; }
 
 }  // extern "C"

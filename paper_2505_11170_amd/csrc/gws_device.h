@@ -228,30 +228,114 @@ __device__ __forceinline__ float byte_to_f32(uint32_t x) {
 // (R = -0 gives -0.0); the fp32 fused multiply-add followed by one RNE to BF16
 // equals the exact BF16 sum.
 // ---------------------------------------------------------------------------
-template <int FMT>
-__device__ __forceinline__ u32x4 sample_group(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
+struct GroupMagnitudes {
+  float m[8];  // |R| of element k as fp32
+};
+
+__device__ __forceinline__ GroupMagnitudes group_magnitudes(const Noise& n) {
   const uint32_t mag = n.nz + n.m2;  // per nibble: |R| in {0, 1, 2}
   const uint32_t me = opaque(mag & 0x0F0F0F0Fu);         // byte i: |R| of nibble 2i
   const uint32_t mo = opaque((mag >> 4) & 0x0F0F0F0Fu);  // byte i: |R| of nibble 2i+1
   // element 2d sits in nibble d, element 2d+1 in nibble d+4
-  const float m[8] = {byte_to_f32<0>(me), byte_to_f32<2>(me), byte_to_f32<0>(mo), byte_to_f32<2>(mo),
-                      byte_to_f32<1>(me), byte_to_f32<3>(me), byte_to_f32<1>(mo), byte_to_f32<3>(mo)};
+  return GroupMagnitudes{{byte_to_f32<0>(me), byte_to_f32<2>(me), byte_to_f32<0>(mo), byte_to_f32<2>(mo),
+                          byte_to_f32<1>(me), byte_to_f32<3>(me), byte_to_f32<1>(mo), byte_to_f32<3>(mo)}};
+}
+
+// bf16_rne(w + R * s) for elements 2d and 2d+1 of a group (register d), packed.
+template <int D>
+__device__ __forceinline__ uint32_t sampled_pair(uint32_t wd, const GroupMagnitudes& g, const Noise& n,
+                                                 const BlockScale& b) {
+  constexpr int n_lo = D, n_hi = D + 4;
+  // s with the sign bit of the nibble: (x3 << sh) & 0x80000000 | s, one shift and one bit-op
+  const uint32_t sh_lo = n.x3 << (28 - 4 * n_lo);
+  const uint32_t sh_hi = (n_hi == 7) ? n.x3 : (n.x3 << (28 - 4 * n_hi));
+  const float s_lo = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_lo, 0x80000000u, b.s_bits, 0xEA));
+  const float s_hi = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_hi, 0x80000000u, b.s_bits, 0xEA));
+  const float w_lo = __uint_as_float(wd << 16), w_hi = __uint_as_float(wd & 0xFFFF0000u);
+  const float sum_lo = __fmaf_rn(g.m[2 * D], s_lo, w_lo);
+  const float sum_hi = __fmaf_rn(g.m[2 * D + 1], s_hi, w_hi);
+  return pack_bf16_rne(sum_lo, sum_hi);
+}
+
+template <int FMT>
+__device__ __forceinline__ u32x4 sample_group(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
+  const GroupMagnitudes g = group_magnitudes(n);
   i16x2 chain = {0, 0};
   u32x4 out;
+  out[0] = cast_pair<FMT>(sampled_pair<0>(w[0], g, n, b), b, hw, chain);
+  out[1] = cast_pair<FMT>(sampled_pair<1>(w[1], g, n, b), b, hw, chain);
+  out[2] = cast_pair<FMT>(sampled_pair<2>(w[2], g, n, b), b, hw, chain);
+  out[3] = cast_pair<FMT>(sampled_pair<3>(w[3], g, n, b), b, hw, chain);
+  return out;
+}
+
+// ---------------------------------------------------------------------------
+// The same group as microscaling element codes (OCP MX: FP8 E4M3 with bias 7,
+// FP6 E3M2 with bias 3) of q / X, X the block's power-of-two scale.
+// ---------------------------------------------------------------------------
+struct MxCodes {
+  uint32_t lo, hi;  // FP8: 8 code bytes.  FP6: 8 codes of 6 bits, element k in bits [6k, 6k+6)
+};
+
+// Code of a BF16 value under the block scale, in plain arithmetic.  Adding
+// 2^(23 - M) times the binade (the binade of the value, or the lowest normal one
+// of X * format below it) makes the fp32 adder round the value to nearest even
+// onto the format's grid and leaves the count of grid steps, k, in the low
+// mantissa bits; the code is that count on top of the binade's first code.
+template <int M, int EBITS, uint32_t MAXCODE>
+__device__ __forceinline__ uint32_t encode_scaled(uint32_t h16, const BlockScale& b) {
+  const uint32_t u = h16 << 16;
+  const uint32_t au = u & 0x7FFFFFFFu;
+  uint32_t eb = au & 0x7F800000u;
+  eb = eb > b.emin_b ? eb : b.emin_b;
+  const uint32_t cb = eb + ((uint32_t)(23 - M) << 23);
+  const float t = __uint_as_float(au) + __uint_as_float(cb);
+  const uint32_t k = __float_as_uint(t) - cb;            // 0 .. 2^(M+1)
+  uint32_t code = ((eb - b.emin_b) >> (23 - M)) + k;     // (E - 1) << M, plus k
+  code = code < MAXCODE ? code : MAXCODE;                // saturate at the largest finite code
+  return code | ((u >> 31) << (M + EBITS));
+}
+
+template <int FMT>
+__device__ __forceinline__ MxCodes sample_group_mx(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
+  static_assert(FMT == 1 || FMT == 2, "MX output exists for the FP8 and FP6 targets");
+  const GroupMagnitudes g = group_magnitudes(n);
+  const uint32_t pk[4] = {sampled_pair<0>(w[0], g, n, b), sampled_pair<1>(w[1], g, n, b),
+                          sampled_pair<2>(w[2], g, n, b), sampled_pair<3>(w[3], g, n, b)};
+  MxCodes c;
+  if (FMT == 1 && hw) {
+    // hardware converter: rounds to nearest even under the scale; each call fills one
+    // 16-bit half of its destination register
+    bf16x2 v[4];
+    __builtin_memcpy(v, pk, 16);
+    i16x2 a = {0, 0}, h = {0, 0};
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(a, v[0], b.x_scale, false);
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(a, v[1], b.x_scale, true);
+    h = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(h, v[2], b.x_scale, false);
+    h = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(h, v[3], b.x_scale, true);
+    __builtin_memcpy(&c.lo, &a, 4);
+    __builtin_memcpy(&c.hi, &h, 4);
+    return c;
+  }
+  uint32_t e[8];
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    const int n_lo = d, n_hi = d + 4;
-    // s with the sign bit of the nibble: (x3 << sh) & 0x80000000 | s, one shift and one bit-op
-    const uint32_t sh_lo = n.x3 << (28 - 4 * n_lo);
-    const uint32_t sh_hi = (n_hi == 7) ? n.x3 : (n.x3 << (28 - 4 * n_hi));
-    const float s_lo = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_lo, 0x80000000u, b.s_bits, 0xEA));
-    const float s_hi = __uint_as_float(__builtin_amdgcn_bitop3_b32(sh_hi, 0x80000000u, b.s_bits, 0xEA));
-    const float w_lo = __uint_as_float(w[d] << 16), w_hi = __uint_as_float(w[d] & 0xFFFF0000u);
-    const float sum_lo = __fmaf_rn(m[2 * d], s_lo, w_lo);
-    const float sum_hi = __fmaf_rn(m[2 * d + 1], s_hi, w_hi);
-    out[d] = cast_pair<FMT>(pack_bf16_rne(sum_lo, sum_hi), b, hw, chain);
+    if (FMT == 1) {
+      e[2 * d] = encode_scaled<3, 4, 0x7Eu>(pk[d] & 0xFFFFu, b);
+      e[2 * d + 1] = encode_scaled<3, 4, 0x7Eu>(pk[d] >> 16, b);
+    } else {
+      e[2 * d] = encode_scaled<2, 3, 0x1Fu>(pk[d] & 0xFFFFu, b);
+      e[2 * d + 1] = encode_scaled<2, 3, 0x1Fu>(pk[d] >> 16, b);
+    }
   }
-  return out;
+  if (FMT == 1) {
+    c.lo = e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24);
+    c.hi = e[4] | (e[5] << 8) | (e[6] << 16) | (e[7] << 24);
+  } else {
+    c.lo = e[0] | (e[1] << 6) | (e[2] << 12) | (e[3] << 18) | (e[4] << 24) | (e[5] << 30);
+    c.hi = (e[5] >> 2) | (e[6] << 4) | (e[7] << 10);
+  }
+  return c;
 }
 
 // sum over one group of g .* (2R), two elements per v_dot2 (products exact, fp32

@@ -16,7 +16,8 @@ constexpr int kMaxTensorsPerLaunch = 56;
 // One tensor as a kernel sees it.  p0..p3 are, for the forward pass,
 // (w, w_hat, bt-or-b_i, scale) and, for the backward pass, (g, dw-or-NULL,
 // dbt-or-db_i, scale); p4 is the backward pass's b_i (NULL: the gradient asked
-// for is dL/db_t itself).
+// for is dL/db_t itself).  The forward pass with MX output carries the element
+// codes in p1 (row stride ldc bytes) and the E8M0 block scales in p4.
 // The bitwidth a block uses is b_t = b_target + v * b_delta (paper Eq. 11) with v
 // the value read through p2; a plain b_t input is the case b_target = 0,
 // b_delta = 1, which leaves every finite value as it is.
@@ -25,14 +26,14 @@ struct TileDesc {
   void* p1;
   void* p2;
   void* p3;
-  const float* p4;
+  void* p4;
   uint32_t rows, cols, ld;
   uint32_t row0, cg0;          // shard origin: row offset, column-group (col0 / 8) offset
   uint32_t seed_lo, seed_hi;
   uint32_t tiles_x;            // workgroup tiles per block row = ceil(cols / 256)
   float b_target, b_delta;     // Eq. 11: b_delta = b_init - b_target
   float lambda_m;              // Eq. 12: lambda / (blocks of the layer); backward only
-  uint32_t reserved;
+  uint32_t ldc;                // MX output: bytes per row of element codes
 };
 static_assert(sizeof(TileDesc) == 88, "descriptor layout");
 
@@ -50,7 +51,7 @@ struct LaunchArgs {
 };
 static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the size verified on the device");
 
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, hipStream_t stream);
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, hipStream_t stream);
 int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_noise_packed(uint32_t* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0,
                         uint64_t seed, uint64_t step, hipStream_t stream);

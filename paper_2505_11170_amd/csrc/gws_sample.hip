@@ -39,7 +39,8 @@ __device__ __forceinline__ void locate(const LaunchArgs& a, int& ti, uint32_t& b
   bx = local - byg * a.t[ti].tiles_x;
 }
 
-template <int FMT>
+// MX: write element codes and E8M0 block scales instead of the BF16 container.
+template <int FMT, bool MX = false>
 __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
   int ti;
   uint32_t byg, bx;
@@ -57,8 +58,8 @@ __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a
   // first tile loaded ahead of the loop: the common one-tile case stays straight-line code
   Tile t = load_tile(w, d, by0, col_base, col, r0);
   for (uint32_t by = by0;;) {
-    if (t.full) fwd_tile<FMT, true>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
-    else fwd_tile<FMT, false>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    if (t.full) fwd_tile<FMT, true, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    else fwd_tile<FMT, false, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
     if (++by >= by_end) break;
     t = load_tile(w, d, by, col_base, col, r0);
   }
@@ -104,7 +105,7 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
     if (d.p4 != nullptr) {
       // dL'/db_i, Eq. 11 and Eq. 12: b_t is recomputed exactly as the forward pass formed it,
       // the subgradient of |b_t - b_target| at 0 is taken as 0
-      const float btv = __fadd_rn(d.b_target, __fmul_rn(d.p4[blk], d.b_delta));
+      const float btv = __fadd_rn(d.b_target, __fmul_rn(((const float*)d.p4)[blk], d.b_delta));
       const float sgn = btv > d.b_target ? 1.0f : (btv < d.b_target ? -1.0f : 0.0f);
       grad = d.b_delta * (grad + d.lambda_m * sgn);
     }
@@ -154,8 +155,16 @@ __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict_
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, hipStream_t stream) {
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
+  if (mx) {
+    switch (fmt) {
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      default: return GWS_ERR_FORMAT;
+    }
+    return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+  }
   switch (fmt) {
     case GWS_FMT_BF16: hipLaunchKernelGGL(sample_fwd_kernel<0>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
     case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL(sample_fwd_kernel<1>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;

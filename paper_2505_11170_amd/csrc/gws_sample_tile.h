@@ -67,9 +67,44 @@ __device__ __forceinline__ Tile load_tile(const uint16_t* __restrict__ src, cons
   return t;
 }
 
+// Element codes of one group to memory.  FP8: 8 bytes at column col.  FP6: 6 bytes at
+// (col / 8) * 6, written as three 2-byte stores (a row of codes is only 2-byte aligned).
+// nv < 8: only the bytes that hold existing elements (unused bits of the last one are 0).
+template <int FMT>
+__device__ __forceinline__ void store_codes(uint8_t* row, uint32_t col, const MxCodes c, int nv) {
+  if (FMT == 1) {
+    uint8_t* dst = row + col;
+    if (nv == 8) {
+      typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+      __builtin_nontemporal_store(u32x2{c.lo, c.hi}, (u32x2*)dst);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k < nv) dst[k] = (uint8_t)((k < 4 ? c.lo : c.hi) >> (8 * (k & 3)));
+    }
+  } else {
+    uint8_t* dst = row + (col >> 3) * 6;
+    if (nv == 8) {
+      uint16_t* d16 = (uint16_t*)dst;
+      __builtin_nontemporal_store((uint16_t)c.lo, d16);
+      __builtin_nontemporal_store((uint16_t)(c.lo >> 16), d16 + 1);
+      __builtin_nontemporal_store((uint16_t)c.hi, d16 + 2);
+    } else {
+      // the fields of elements past the edge hold noise: clear them
+      const uint64_t bits = (((uint64_t)c.hi << 32) | c.lo) & (((uint64_t)1 << (6 * nv)) - 1);
+      const int nbytes = (nv * 6 + 7) >> 3;
+#pragma unroll
+      for (int k = 0; k < 6; ++k)
+        if (k < nbytes) dst[k] = (uint8_t)(bits >> (8 * k));
+    }
+  }
+}
+
 // STREAM: w_hat is written with streaming (non-temporal) stores, right for a pass
 // that is not consumed at once; off, the stores stay in cache for a reader that follows.
-template <int FMT, bool FULL, bool STREAM = true>
+// MX: the output is element codes (p1, row stride ldc) and E8M0 block scales (p4)
+// instead of the BF16 container.
+template <int FMT, bool FULL, bool STREAM = true, bool MX = false>
 __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
                                          uint32_t by, uint32_t col_base, uint32_t lane) {
   const uint32_t row_base = by * 32;
@@ -102,7 +137,11 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   BlockScale b = block_scale(a16, btv);
   if (FMT == 1) cast_constants<8, -6>(a16, b);
   if (FMT == 2) cast_constants<4, -2>(a16, b);
-  if (block_exists && (gc & 3) == 0 && r0 == 0) scale[(size_t)by * nbc + bcol] = b.s32;
+  if (block_exists && (gc & 3) == 0 && r0 == 0) {
+    scale[(size_t)by * nbc + bcol] = b.s32;
+    // shared exponent of the block: biased exponent of X; X = 1 for an all-zero block
+    if (MX) ((uint8_t*)d.p4)[(size_t)by * nbc + bcol] = a16 ? (uint8_t)(__float_as_uint(b.x_scale) >> 23) : (uint8_t)127;
+  }
   // hardware FP8 converters only if neither block of this wavefront can overflow
   const bool hw = (FMT == 1) && (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0);
 
@@ -114,13 +153,18 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
       if (!FULL && t.nv[i] == 0) continue;
       const uint32_t row = row_base + r0 + 8 * i;
       const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
-      const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
-      uint16_t* dst = w_hat + (size_t)row * d.ld + col;
-      if (FULL || t.nv[i] == 8) {
-        if (STREAM) store16(dst, o);
-        else *(u32x4*)dst = o;
+      if constexpr (MX) {
+        const MxCodes c = sample_group_mx<FMT>(t.v[i], n, b, use_hw);
+        store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
       } else {
-        store_partial(dst, o, t.nv[i]);
+        const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
+        uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+        if (FULL || t.nv[i] == 8) {
+          if (STREAM) store16(dst, o);
+          else *(u32x4*)dst = o;
+        } else {
+          store_partial(dst, o, t.nv[i]);
+        }
       }
     }
   };
