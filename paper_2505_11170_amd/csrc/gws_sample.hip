@@ -76,6 +76,18 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   const float* __restrict__ scale = (const float*)d.p3;
   const uint32_t cg = d.cg0 + (col >> 3);
 
+  // the block's lane that writes the gradient fetches what it needs first, so the
+  // loads are in flight while the noise is regenerated
+  const uint32_t nbc = (d.cols + 31) >> 5;
+  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
+  const bool writer = (FULL || bcol < nbc) && (gc & 3) == 0 && r0 == 0;
+  const size_t blk = (size_t)by * nbc + bcol;
+  float s32 = 0.0f, bi = 0.0f;
+  if (writer) {
+    s32 = scale[blk];
+    if (d.p4 != nullptr) bi = ((const float*)d.p4)[blk];
+  }
+
   // sum_{b_l}(g .* R), accumulated as sum(g .* 2R) / 2: every product is exact
   // in fp32, the order of the additions is fixed (per lane group by group, two
   // elements per step, then the lane tree), so the result is reproducible.
@@ -95,17 +107,13 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   }
   acc = block_sum_f32(acc) * 0.5f;
 
-  const uint32_t nbc = (d.cols + 31) >> 5;
-  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
-  if ((FULL || bcol < nbc) && (gc & 3) == 0 && r0 == 0) {
-    const size_t blk = (size_t)by * nbc + bcol;
-    const float s32 = scale[blk];
+  if (writer) {
     const float neg_ln2 = __uint_as_float(0xBF317218u);  // -ln 2
     float grad = (neg_ln2 * s32) * acc;                  // dL/db_t, Eq. 4
     if (d.p4 != nullptr) {
       // dL'/db_i, Eq. 11 and Eq. 12: b_t is recomputed exactly as the forward pass formed it,
       // the subgradient of |b_t - b_target| at 0 is taken as 0
-      const float btv = __fadd_rn(d.b_target, __fmul_rn(((const float*)d.p4)[blk], d.b_delta));
+      const float btv = __fadd_rn(d.b_target, __fmul_rn(bi, d.b_delta));
       const float sgn = btv > d.b_target ? 1.0f : (btv < d.b_target ? -1.0f : 0.0f);
       grad = d.b_delta * (grad + d.lambda_m * sgn);
     }
