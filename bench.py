@@ -213,6 +213,16 @@ def main():
         out["cpu_baseline"] = {"value": sp * passes / dt, "unit": "params/s", "cores": cores, "kind": "oracle",
                                "sample": f"first {len(sample)} tensors of the workload ({sp} params), {passes} fwd+bwd "
                                          f"steps, {dt:.2f} s wall on {cores} threads"}
+        # the same oracle on one thread, on the first tensor only
+        oracle.set_threads(1)
+        w, bt, g, seed = host[0]
+        t0 = time.perf_counter()
+        _, sc = oracle.sample_fwd(w, bt, oracle.FMT_FP8_E4M3, seed, 0)
+        oracle.sample_bwd(g, sc, seed, 0)
+        dt1 = time.perf_counter() - t0
+        oracle.set_threads(0)
+        out["cpu_baseline"]["single_thread"] = {"value": sample[0].rows * sample[0].cols / dt1, "unit": "params/s",
+                                                "sample": f"first tensor ({sample[0].rows}x{sample[0].cols}), {dt1:.2f} s"}
     del res
 
     # ---- extras: other configurations, outside the timed region ----
@@ -247,6 +257,17 @@ def main():
             torch.cuda.empty_cache()
         except Exception as e:  # pragma: no cover
             extras["parametrised_bitwidth_error"] = repr(e)
+        try:
+            # config 1: one 768x768 weight, forward only; a latency-bound launch
+            t1 = synth.make_tensor(0, 768, 768, bt=6.0, device=dev, with_grad=False)
+            d1 = gws.pack([gws.TensorDesc(rows=768, cols=768, seed=gws.gws_derive_seed(0, 0), w=t1["w"],
+                                          w_hat=torch.empty_like(t1["w"]), bt=t1["bt"],
+                                          scale=torch.empty(24, 24, device=dev))])
+            ms1 = _time_ms(torch, lambda: gws.gws_sample_fwd(d1, gws.FMT_FP8_E4M3, 0), 200, warmup=20)
+            extras["config1_768x768_fwd"] = {"us_per_call_back_to_back": ms1 * 1e3,
+                                             "GBps": (4.0 * 768 * 768 + 8 * 576) / ms1 / 1e6}
+        except Exception as e:  # pragma: no cover
+            extras["config1_error"] = repr(e)
         try:
             extras["mx_output"] = mx_bench(torch, gws, synth, dev, shapes, params)
         except Exception as e:  # pragma: no cover

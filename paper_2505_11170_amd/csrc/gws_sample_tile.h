@@ -168,7 +168,63 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
       }
     }
   };
-  if (FMT == 1 && hw) finish(true);
+  // FP6-E3M2: the 32-wide hardware converters (v_cvt_scalef32_pk32_bf6_bf16 and back) take
+  // a lane's whole tile at once, round to nearest even with gradual underflow and saturate
+  // at 28 * X (checked against the cast's definition on every finite BF16 input at several
+  // scales), so all four groups are sampled first and converted together.
+  auto finish_fp6 = [&]() {
+    typedef __bf16 bf16x32 __attribute__((ext_vector_type(32)));
+    typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+    uint32_t pk[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (!FULL && t.nv[i] == 0) {
+        pk[4 * i] = pk[4 * i + 1] = pk[4 * i + 2] = pk[4 * i + 3] = 0;
+        continue;
+      }
+      const Noise n = group_noise(cg, d.row0 + row_base + r0 + 8 * i, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const GroupMagnitudes g = group_magnitudes(n);
+      pk[4 * i] = sampled_pair<0>(t.v[i][0], g, n, b);
+      pk[4 * i + 1] = sampled_pair<1>(t.v[i][1], g, n, b);
+      pk[4 * i + 2] = sampled_pair<2>(t.v[i][2], g, n, b);
+      pk[4 * i + 3] = sampled_pair<3>(t.v[i][3], g, n, b);
+    }
+    bf16x32 v;
+    __builtin_memcpy(&v, pk, 64);
+    const u32x6 c = __builtin_amdgcn_cvt_scalef32_pk32_bf6_bf16(v, b.x_scale);
+    if constexpr (MX) {
+      // element k of the lane's 32 sits in bits [6k, 6k + 6): 48 bits per group
+      const MxCodes gc4[4] = {{c[0], c[1] & 0xFFFFu},
+                              {(c[1] >> 16) | (c[2] << 16), c[2] >> 16},
+                              {c[3], c[4] & 0xFFFFu},
+                              {(c[4] >> 16) | (c[5] << 16), c[5] >> 16}};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (!FULL && t.nv[i] == 0) continue;
+        const uint32_t row = row_base + r0 + 8 * i;
+        store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, gc4[i], FULL ? 8 : t.nv[i]);
+      }
+    } else {
+      const bf16x32 q = __builtin_amdgcn_cvt_scalef32_pk32_bf16_bf6(c, b.x_scale);
+      uint32_t o[16];
+      __builtin_memcpy(o, &q, 64);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (!FULL && t.nv[i] == 0) continue;
+        const uint32_t row = row_base + r0 + 8 * i;
+        const u32x4 og = {o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
+        uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+        if (FULL || t.nv[i] == 8) {
+          if (STREAM) store16(dst, og);
+          else *(u32x4*)dst = og;
+        } else {
+          store_partial(dst, og, t.nv[i]);
+        }
+      }
+    }
+  };
+  if constexpr (FMT == 2) finish_fp6();
+  else if (FMT == 1 && hw) finish(true);
   else finish(false);
 }
 
