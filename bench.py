@@ -287,6 +287,14 @@ def main():
             ms1 = _time_ms(torch, lambda: gws.gws_sample_fwd(d1, gws.FMT_FP8_E4M3, 0), 200, warmup=20)
             extras["config1_768x768_fwd"] = {"us_per_call_back_to_back": ms1 * 1e3,
                                              "GBps": (4.0 * 768 * 768 + 8 * 576) / ms1 / 1e6}
+            # the same 20 calls recorded once into a HIP graph and replayed
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(20):
+                    gws.gws_sample_fwd(d1, gws.FMT_FP8_E4M3, 0)
+            msg = _time_ms(torch, graph.replay, 20, warmup=3) / 20
+            extras["config1_768x768_fwd"]["us_per_call_in_a_graph_of_20"] = msg * 1e3
+            del graph
         except Exception as e:  # pragma: no cover
             extras["config1_error"] = repr(e)
         try:

@@ -164,7 +164,9 @@ int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, 
  * multiples of 256 and K of 64, one persistent launch samples every block once
  * (all workgroups together), meets at a device-wide arrival barrier kept in a few
  * device words of the library, and runs the GEMM on w_hat; two such calls must
- * not run concurrently on one GPU.  Otherwise the sampling sits in the weight
+ * not run concurrently on one GPU, and on a stream that is being captured into a
+ * graph the call records the sampling kernel followed by the plain GEMM on w_hat
+ * instead (same bytes, no state).  Otherwise the sampling sits in the weight
  * operand load of every output tile (no w_hat round trip, each block resampled
  * per tile row).  Both give bit-identical w_hat and Y.                          */
 int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,

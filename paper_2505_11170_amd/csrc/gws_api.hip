@@ -255,6 +255,20 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_t
   g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
   g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
   g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
+  // The sample-once kernel tells its calls apart by an epoch passed as a kernel argument; a
+  // captured launch would replay one epoch against the synchronisation words it left behind.
+  // Under stream capture the same bytes come from two stateless launches instead: the
+  // sampling kernel, then the plain GEMM on w_hat.
+  if (linear256_fused_applicable(g)) {
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (stream != nullptr && hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) return GWS_ERR_LAUNCH;
+    if (capture != hipStreamCaptureStatusNone) {
+      rc = run_batched(w, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream);
+      if (rc != GWS_OK) return rc;
+      g.w = g.w_hat;
+      return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+    }
+  }
   return launch_gemm(g, w_is_nk, 1, fmt, (hipStream_t)stream);
 }
 

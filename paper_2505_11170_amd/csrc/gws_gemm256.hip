@@ -307,18 +307,25 @@ bool gemm256_applicable(const GemmArgs& g) {
   return g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 && g.M > 0 && g.N > 0 && g.K > 0;
 }
 
+// The kernels need more dynamic LDS than the default limit; the attribute is raised once per
+// kernel and process (not per launch: nothing but the launch itself is issued on a stream that
+// may be under capture).
+template <class K>
+static bool raise_lds_limit(K kernel, size_t lds) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+}
+
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream) {
   const uint64_t tiles = (uint64_t)(g.M / g256::TM) * (g.N / g256::TN);
   if (tiles >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
   const size_t lds = g256::lds_bytes(w_is_nk != 0);
-  hipError_t e;
   if (w_is_nk) {
-    e = hipFuncSetAttribute((const void*)gemm256_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    static const bool ok = raise_lds_limit(gemm256_kernel<true>, g256::lds_bytes(true));
+    if (!ok) return GWS_ERR_LAUNCH;
     hipLaunchKernelGGL(gemm256_kernel<true>, dim3((uint32_t)tiles), dim3(256), lds, stream, g);
   } else {
-    e = hipFuncSetAttribute((const void*)gemm256_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    static const bool ok = raise_lds_limit(gemm256_kernel<false>, g256::lds_bytes(false));
+    if (!ok) return GWS_ERR_LAUNCH;
     hipLaunchKernelGGL(gemm256_kernel<false>, dim3((uint32_t)tiles), dim3(256), lds, stream, g);
   }
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
@@ -326,14 +333,13 @@ int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream) {
 
 template <int FMT>
 static int launch_fused_fmt(const GemmArgs& g, int w_is_nk, uint32_t grid, size_t lds, uint32_t epoch, hipStream_t s) {
-  hipError_t e;
   if (w_is_nk) {
-    e = hipFuncSetAttribute((const void*)linear256_fused_kernel<FMT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    static const bool ok = raise_lds_limit(linear256_fused_kernel<FMT, true>, g256::lds_bytes(true));
+    if (!ok) return GWS_ERR_LAUNCH;
     hipLaunchKernelGGL((linear256_fused_kernel<FMT, true>), dim3(grid), dim3(256), lds, s, g, epoch);
   } else {
-    e = hipFuncSetAttribute((const void*)linear256_fused_kernel<FMT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return GWS_ERR_LAUNCH;
+    static const bool ok = raise_lds_limit(linear256_fused_kernel<FMT, false>, g256::lds_bytes(false));
+    if (!ok) return GWS_ERR_LAUNCH;
     hipLaunchKernelGGL((linear256_fused_kernel<FMT, false>), dim3(grid), dim3(256), lds, s, g, epoch);
   }
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
