@@ -189,7 +189,9 @@ __device__ __forceinline__ uint32_t cast_scaled_bits(uint32_t h16, const BlockSc
 // Cast of a packed BF16 pair.  FP8-E4M3 goes through the hardware converters
 // (v_cvt_scalef32_pk_fp8_bf16 and back: round to nearest even, gradual
 // underflow, division by the power-of-two scale), which produce NaN instead of
-// saturating, so they are used only where the block cannot overflow.
+// saturating, so they are used only where the block cannot overflow.  FP6-E3M2 is
+// cast in arithmetic here; this per-pair form serves the GEMM kernel's operand
+// path, while the tile code converts FP6 with the 32-wide hardware converters.
 template <int FMT>
 __device__ __forceinline__ uint32_t cast_pair(uint32_t pk, const BlockScale& b, bool hw, i16x2& chain) {
   if (FMT == 0) return pk;
@@ -274,7 +276,7 @@ __device__ __forceinline__ u32x4 sample_group(const u32x4 w, const Noise& n, con
 // FP6 E3M2 with bias 3) of q / X, X the block's power-of-two scale.
 // ---------------------------------------------------------------------------
 struct MxCodes {
-  uint32_t lo, hi;  // FP8: 8 code bytes.  FP6: 8 codes of 6 bits, element k in bits [6k, 6k+6)
+  uint32_t lo, hi;  // FP8: 8 code bytes.  FP6: 8 codes of 6 bits, element k in bits [6k, 6k+6) of hi:lo
 };
 
 // Code of a BF16 value under the block scale, in plain arithmetic.  Adding
@@ -296,14 +298,14 @@ __device__ __forceinline__ uint32_t encode_scaled(uint32_t h16, const BlockScale
   return code | ((u >> 31) << (M + EBITS));
 }
 
-template <int FMT>
-__device__ __forceinline__ MxCodes sample_group_mx(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
-  static_assert(FMT == 1 || FMT == 2, "MX output exists for the FP8 and FP6 targets");
+// FP8-E4M3 codes of one group.  (FP6-E3M2 codes come from the 32-wide converter, a lane's
+// whole tile at a time: see fwd_tile.)
+__device__ __forceinline__ MxCodes sample_group_mx_fp8(const u32x4 w, const Noise& n, const BlockScale& b, bool hw) {
   const GroupMagnitudes g = group_magnitudes(n);
   const uint32_t pk[4] = {sampled_pair<0>(w[0], g, n, b), sampled_pair<1>(w[1], g, n, b),
                           sampled_pair<2>(w[2], g, n, b), sampled_pair<3>(w[3], g, n, b)};
   MxCodes c;
-  if (FMT == 1 && hw) {
+  if (hw) {
     // hardware converter: rounds to nearest even under the scale; each call fills one
     // 16-bit half of its destination register
     bf16x2 v[4];
@@ -317,24 +319,15 @@ __device__ __forceinline__ MxCodes sample_group_mx(const u32x4 w, const Noise& n
     __builtin_memcpy(&c.hi, &h, 4);
     return c;
   }
+  // the block can exceed 448 X, where the converter would give NaN: saturating arithmetic form
   uint32_t e[8];
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    if (FMT == 1) {
-      e[2 * d] = encode_scaled<3, 4, 0x7Eu>(pk[d] & 0xFFFFu, b);
-      e[2 * d + 1] = encode_scaled<3, 4, 0x7Eu>(pk[d] >> 16, b);
-    } else {
-      e[2 * d] = encode_scaled<2, 3, 0x1Fu>(pk[d] & 0xFFFFu, b);
-      e[2 * d + 1] = encode_scaled<2, 3, 0x1Fu>(pk[d] >> 16, b);
-    }
+    e[2 * d] = encode_scaled<3, 4, 0x7Eu>(pk[d] & 0xFFFFu, b);
+    e[2 * d + 1] = encode_scaled<3, 4, 0x7Eu>(pk[d] >> 16, b);
   }
-  if (FMT == 1) {
-    c.lo = e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24);
-    c.hi = e[4] | (e[5] << 8) | (e[6] << 16) | (e[7] << 24);
-  } else {
-    c.lo = e[0] | (e[1] << 6) | (e[2] << 12) | (e[3] << 18) | (e[4] << 24) | (e[5] << 30);
-    c.hi = (e[5] >> 2) | (e[6] << 4) | (e[7] << 10);
-  }
+  c.lo = e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24);
+  c.hi = e[4] | (e[5] << 8) | (e[6] << 16) | (e[7] << 24);
   return c;
 }
 

@@ -148,22 +148,24 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   // ---- noise, add, round, cast, store ----
   const uint32_t cg = d.cg0 + (col >> 3);
   auto finish = [&](bool use_hw) {
+    if constexpr (FMT != 2) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (!FULL && t.nv[i] == 0) continue;
-      const uint32_t row = row_base + r0 + 8 * i;
-      const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
-      if constexpr (MX) {
-        const MxCodes c = sample_group_mx<FMT>(t.v[i], n, b, use_hw);
-        store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
-      } else {
-        const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
-        uint16_t* dst = w_hat + (size_t)row * d.ld + col;
-        if (FULL || t.nv[i] == 8) {
-          if (STREAM) store16(dst, o);
-          else *(u32x4*)dst = o;
+      for (int i = 0; i < 4; ++i) {
+        if (!FULL && t.nv[i] == 0) continue;
+        const uint32_t row = row_base + r0 + 8 * i;
+        const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+        if constexpr (MX) {
+          const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, use_hw);
+          store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
         } else {
-          store_partial(dst, o, t.nv[i]);
+          const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
+          uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+          if (FULL || t.nv[i] == 8) {
+            if (STREAM) store16(dst, o);
+            else *(u32x4*)dst = o;
+          } else {
+            store_partial(dst, o, t.nv[i]);
+          }
         }
       }
     }
