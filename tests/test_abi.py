@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 from paper_2505_11170_amd import binding
-from paper_2505_11170_amd.binding import _CTensor
+from paper_2505_11170_amd.binding import _CBitwidth, _CMxOut, _CTensor
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -88,6 +88,42 @@ def test_argument_validation_launches_nothing(lib):
     assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty
     for s in range(7):
         assert lib.gws_status_string(s)
+
+
+def test_bitwidth_and_mx_entry_points_validate_before_any_launch(lib):
+    OK, NULL, SHAPE, ALIGN, FORMAT, LAUNCH, ALIAS = range(7)
+    fake = 0x10000  # never dereferenced: every case below fails validation first
+    base = dict(w=fake, w_hat=fake + 0x100000, bt=fake, scale=fake, g=fake, dw=None, dbt=fake,
+                rows=64, cols=64, ld=64, row0=0, col0=0, seed=1)
+    bw = (_CBitwidth * 1)()
+    bw[0].b_init, bw[0].b_target, bw[0].lam, bw[0].layer_blocks = 6.0, 4.0, 0.0, 0
+
+    def arr(**over):
+        return (_CTensor * 1)(_t(**{**base, **over}))
+
+    assert lib.gws_sample_fwd_bi(arr(), 1, None, 1, 0, None) == NULL           # no bitwidth settings
+    assert lib.gws_sample_fwd_bi(None, 0, None, 1, 0, None) == OK              # empty list
+    assert lib.gws_sample_fwd_bi(arr(), 1, bw, 7, 0, None) == FORMAT
+    assert lib.gws_sample_fwd_bi(arr(bt=None), 1, bw, 1, 0, None) == NULL
+    assert lib.gws_sample_bwd_bi(arr(bt=None), 1, bw, 0, None) == NULL         # backward needs b_i here
+    assert lib.gws_sample_bwd_bi(arr(bt=fake + 2), 1, bw, 0, None) == ALIGN
+    bw[0].layer_blocks = -1
+    assert lib.gws_sample_bwd_bi(arr(), 1, bw, 0, None) == SHAPE
+    assert lib.gws_sample_bwd_bi(arr(rows=0), 1, bw, 0, None) == SHAPE         # checked for every tensor, empty or not
+
+    def mx(fmt=1, codes=fake + 0x200000, xscale=fake, ldc=64, **over):
+        o = (_CMxOut * 1)()
+        o[0].codes, o[0].xscale, o[0].ldc = codes, xscale, ldc
+        return lib.gws_sample_fwd_mx(arr(**over), o, 1, fmt, 0, None)
+
+    assert mx(fmt=0) == FORMAT and mx(fmt=3) == FORMAT                         # MX exists for FP8 and FP6 only
+    assert mx(codes=None) == NULL and mx(xscale=None) == NULL and mx(w=None) == NULL
+    assert mx(w_hat=None, rows=0) == OK                                        # w_hat is not used; empty tensors are skipped
+    assert mx(ldc=56) == SHAPE and mx(ldc=68) == SHAPE                         # FP8: >= cols, multiple of 8
+    assert mx(fmt=2, ldc=46) == SHAPE and mx(fmt=2, ldc=49) == SHAPE           # FP6: >= 48 bytes, even
+    assert mx(codes=fake + 0x200004) == ALIGN and mx(fmt=2, ldc=48, codes=fake + 0x200001) == ALIGN
+    assert mx(codes=fake + 128) == ALIAS                                       # codes inside w
+    assert lib.gws_sample_fwd_mx(arr(), None, 1, 1, 0, None) == NULL
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -100,6 +100,23 @@ def test_edge_values_and_zero_blocks(fmt):
     check_mx([item], fmt, 3)
 
 
+@pytest.mark.parametrize("fmt", MX_FMTS)
+def test_config2_all_48_weights_in_one_launch(fmt):
+    # the launch configuration bench.py times; the oracle checks one tensor of each shape in full
+    shapes = [(s.rows, s.cols) for s in synth.gpt2_124m_shapes()]
+    items = make_items(shapes, 0)
+    res = run_mx(items, fmt, 1)
+    seen = set()
+    for it, (codes, xscale, scale, ldc) in zip(items, res):
+        if (it["rows"], it["cols"]) in seen:
+            continue
+        seen.add((it["rows"], it["cols"]))
+        ref_c, ref_x, ref_s = oracle.sample_fwd_mx(synth.bits(it["w"]), it["bt"].numpy(), fmt, it["seed"], 1, ldc=ldc)
+        assert np.array_equal(scale.view(np.uint32), ref_s.view(np.uint32))
+        assert np.array_equal(xscale, ref_x) and np.array_equal(codes, ref_c), (it["rows"], it["cols"])
+    assert len(seen) == 4
+
+
 def test_shard_origin_reproduces_the_unsharded_codes():
     r, c = 128, 256
     item = make_items([(r, c)], 450)[0]
