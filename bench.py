@@ -415,7 +415,24 @@ def linear_bench(torch, gws, synth, dev):
         gws.gws_sample_fwd(pk, fmt, 0)
         torch.matmul(x, w_hat, out=y)
 
+    # backward of the same linear: dW = X^T dY [K x N], with dL/db_t from the GEMM's epilogue or from the
+    # separate backward kernel on the stored dW
+    dy = (synth.make_activation(6, M, N, device=dev).float() * 1e-3).to(torch.bfloat16)
+    dw = torch.empty_like(w)
+    dbt = torch.empty_like(scale)
+    d_bwd = gws.TensorDesc(rows=K, cols=N, seed=seed, scale=scale, dw=dw, dbt=dbt)
+    d_bwd_plain = gws.TensorDesc(rows=K, cols=N, seed=seed, dw=dw)
+    pk_bwd = gws.pack([gws.TensorDesc(rows=K, cols=N, seed=seed, scale=scale, g=dw, dw=dw, dbt=dbt)])
+
+    def bwd_unfused():
+        gws.gws_linear_bwd_w(x, dy, d_bwd_plain, 0)
+        gws.gws_sample_bwd(pk_bwd, 0)
+
     variants = {
+        "bwd_w_fused": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd, 0),
+        "bwd_w_plain": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd_plain, 0),
+        "bwd_w_unfused": bwd_unfused,
+        "bwd_w_torch": lambda: torch.matmul(x.t(), dy, out=dw),
         "fused": lambda: gws.gws_linear_fwd(x, d_full, y, fmt, 0),
         "unfused": unfused,
         "plain": lambda: gws.gws_gemm_bf16(x, w, y),
@@ -446,6 +463,11 @@ def linear_bench(torch, gws, synth, dev):
             "unfused_torch_gemm_ms": t_unfused_torch, "sample_only_ms": t_sample,
             "plain_own_ms": t_plain, "plain_own_on_w_hat_ms": t_plain_what,
             "plain_torch_ms": t_torch, "plain_torch_on_w_hat_ms": t_torch_what,
+            "bwd_w": {"gemm_with_dbt_epilogue_ms": med["bwd_w_fused"], "gemm_plain_ms": med["bwd_w_plain"],
+                      "gemm_plain_then_sample_bwd_ms": med["bwd_w_unfused"], "torch_matmul_ms": med["bwd_w_torch"],
+                      "epilogue_overhead_pct": 100.0 * (med["bwd_w_fused"] - med["bwd_w_plain"]) / med["bwd_w_plain"],
+                      "separate_kernel_overhead_pct": 100.0 * (med["bwd_w_unfused"] - med["bwd_w_plain"]) / med["bwd_w_plain"],
+                      "TFLOPs_with_epilogue": 2.0 * M * K * N / med["bwd_w_fused"] / 1e9},
             "fused_overhead_pct_vs_own_plain": 100.0 * (t_fused - t_plain) / t_plain,
             "fused_overhead_pct_vs_best_plain": 100.0 * (t_fused - best_plain) / best_plain,
             "unfused_overhead_pct_vs_own_plain": 100.0 * (t_unfused - t_plain) / t_plain,

@@ -173,6 +173,23 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
                    const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
                    void* y, int64_t ldy, void* stream);
 
+/* Weight gradient of the sampled-weight linear with the reduction of Eq. 4 in the GEMM's
+ * epilogue (the linear's backward pass, paper Eq. 2, applied to w_hat):
+ *   dW      = X^T * dY                 fp32 accumulation, one round-to-nearest-even to BF16
+ *   dL/db_t = -ln2 * s32 * sum_{b_l}( dW .* R )        on the rounded BF16 dW, fp32
+ * so that dL/db_t costs no second pass over dW.  (dX = dY * w_hat^T is gws_gemm_bf16 on
+ * w_hat with the other layout flag.)
+ *   x  : device BF16 [M x K] (ldx), the linear's input;  dy : device BF16 [M x N] (ldy)
+ *   w  : one descriptor (host) of the weight as stored: [K x N] (rows = K, cols = N) or,
+ *        when w_is_nk != 0, [N x K].  Fields used: dw (out, required, [rows x ld]),
+ *        dbt (out; NULL = plain GEMM), scale (in, required with dbt), rows, cols, ld,
+ *        row0, col0, seed.
+ * rows and cols must be multiples of 256 and M a multiple of 64 (GWS_ERR_SHAPE otherwise);
+ * M == 0 is an error, since dW would be undefined.  Given the same dW bytes,
+ * gws_sample_bwd returns the same dL/db_t up to the order of the fp32 additions.        */
+int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy,
+                     const gws_tensor* w, int w_is_nk, uint64_t step, void* stream);
+
 /* Plain BF16 GEMM with the same tiling as gws_linear_fwd and no sampling:
  * Y = X * W (or X * W^T when w_is_nk).  The reference point the fused kernel's
  * overhead is measured against.  w is device BF16 with leading dimension ldw.     */

@@ -16,7 +16,7 @@ _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 
-EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd",
+EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_bwd_w",
            "gws_gemm_bf16", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
 
 
@@ -110,6 +110,8 @@ def load_library() -> ctypes.CDLL:
     L.gws_sample_fwd_mx.restype = ci
     L.gws_linear_fwd.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
     L.gws_linear_fwd.restype = ci
+    L.gws_linear_bwd_w.argtypes = [vp, vp, i64, i64, i64, tp, ci, u64, vp]
+    L.gws_linear_bwd_w.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
     L.gws_gemm_bf16.restype = ci
     L.gws_noise_packed.argtypes = [vp, i64, i64, i64, i64, u64, u64, vp]
@@ -172,7 +174,7 @@ def _marshal(descs: Sequence[TensorDesc]):
     for c, d in zip(arr, descs):
         ld = d.ld
         if ld is None:
-            ref = d.w if d.w is not None else d.g
+            ref = next((t for t in (d.w, d.g, d.dw) if t is not None), None)
             ld = int(ref.stride(0)) if ref is not None and ref.dim() == 2 else d.cols
         c.w, c.w_hat, c.bt, c.scale = _p(d.w), _p(d.w_hat), _p(d.bt), _p(d.scale)
         c.g, c.dw, c.dbt = _p(d.g), _p(d.dw), _p(d.dbt)
@@ -274,6 +276,13 @@ def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = Fal
     M, K = int(x.shape[0]), int(x.shape[1])
     _check(L.gws_linear_fwd(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt),
                             int(step), _p(y), int(y.stride(0)), _stream(stream)), "gws_linear_fwd")
+
+
+def gws_linear_bwd_w(x, dy, w: TensorDesc, step: int, w_is_nk: bool = False, stream=None) -> None:
+    """dW = X^T dY into ``w.dw`` and, when ``w.dbt`` is given, dL/db_t (paper Eq. 4) from the GEMM's epilogue."""
+    L = load_library()
+    _check(L.gws_linear_bwd_w(_p(x), _p(dy), int(x.shape[0]), int(x.stride(0)), int(dy.stride(0)), _marshal([w]),
+                              int(bool(w_is_nk)), int(step), _stream(stream)), "gws_linear_bwd_w")
 
 
 def gws_gemm_bf16(x, w, y, w_is_nk: bool = False, stream=None) -> None:

@@ -272,6 +272,35 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_t
   return launch_gemm(g, w_is_nk, 1, fmt, (hipStream_t)stream);
 }
 
+int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w,
+                     int w_is_nk, uint64_t step, void* stream) {
+  if (!w) return GWS_ERR_NULL;
+  int rc = check_shape(*w);
+  if (rc != GWS_OK) return rc;
+  const int64_t K = w_is_nk ? w->cols : w->rows, N = w_is_nk ? w->rows : w->cols;
+  if (M <= 0 || M >= (int64_t)1 << 31 || (M & 63) != 0) return GWS_ERR_SHAPE;
+  if (w->rows <= 0 || w->cols <= 0 || (w->rows & 255) != 0 || (w->cols & 255) != 0) return GWS_ERR_SHAPE;
+  if (ldx < K || ldy < N || (ldx & 7) != 0 || (ldy & 7) != 0 || ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (!x || !dy || !w->dw) return GWS_ERR_NULL;
+  if (w->dbt && !w->scale) return GWS_ERR_NULL;
+  if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(w->dw, 16) || !aligned(w->dbt, 4) || !aligned(w->scale, 4)) return GWS_ERR_ALIGN;
+  const size_t dw_bytes = (size_t)w->rows * w->ld * 2;
+  if (overlap2(w->dw, dw_bytes, x, (size_t)M * ldx * 2) || overlap2(w->dw, dw_bytes, dy, (size_t)M * ldy * 2)) return GWS_ERR_ALIAS;
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  // C[rows x cols] = A^T B over the M tokens: A supplies the rows of the stored weight
+  g.x = (const uint16_t*)(w_is_nk ? dy : x); g.ldx = (uint32_t)(w_is_nk ? ldy : ldx);
+  g.w = (const uint16_t*)(w_is_nk ? x : dy); g.ldw = (uint32_t)(w_is_nk ? ldx : ldy);
+  g.y = (uint16_t*)w->dw; g.ldy = (uint32_t)w->ld;
+  g.M = (uint32_t)w->rows; g.N = (uint32_t)w->cols; g.K = (uint32_t)M;
+  g.scale = w->scale; g.dbt = w->dbt;
+  g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
+  g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
+  g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
+  if (!gemm256_tn_applicable(g)) return GWS_ERR_SHAPE;
+  return launch_gemm256_tn(g, w->dbt != nullptr, (hipStream_t)stream);
+}
+
 int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
                   int w_is_nk, void* y, int64_t ldy, void* stream) {
   if (M < 0 || K < 0 || N < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
@@ -316,6 +345,6 @@ const char* gws_status_string(int status) {
   }
 }
 
-int gws_version(void) { return 3; }
+int gws_version(void) { return 4; }
 
 }  // extern "C"

@@ -20,32 +20,10 @@
 #include <atomic>
 
 #include "gws_launch.h"
+#include "gws_mfma.h"
 #include "gws_sample_tile.h"
 
 namespace gws {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-namespace g256 {
-constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int PA = TK + 8;        // A / [N x K] pitch in elements (144 B)
-constexpr int PB_KN = TN + 16;    // [K x N] pitch in elements (544 B)
-constexpr int A_STAGE = TM * PA;                  // elements
-constexpr int B_STAGE_NK = TN * PA;
-constexpr int B_STAGE_KN = TK * PB_KN;
-constexpr int PC = 128 + 8;       // epilogue pitch per wavefront tile (elements)
-constexpr size_t lds_bytes(bool nk) {
-  return (size_t)2 * (2 * A_STAGE + 2 * (nk ? B_STAGE_NK : B_STAGE_KN));
-}
-}  // namespace g256
-
-union Frag8 {
-  u32x4 u;
-  bf16x8 v;
-  i16x4 h[2];
-};
 
 // One 256 x 256 output tile.  `L` is the launch-order tile number (remapped below),
 // `wsrc` the weight operand (W, or the sampled w_hat).
@@ -60,21 +38,8 @@ __device__ __forceinline__ void gemm256_tile(const GemmArgs& g, const uint16_t* 
   const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const uint32_t wm = wave >> 1, wn = wave & 1;
 
-  // ---- tile numbering: XCD-contiguous ranges of an (8 m x 4 n)-patch order ----
-  const uint32_t mt = g.M / TM, nt = g.N / TN, total = mt * nt;
-  {
-    const uint32_t per = total / 8, rem = total % 8, x = L % 8, j = L / 8;
-    // XCD x owns `per` tiles (+1 for the first `rem`); its range starts at:
-    L = x * per + (x < rem ? x : rem) + j;
-  }
   uint32_t tile_m, tile_n;
-  {
-    const uint32_t band_sz = 8 * nt;                 // tiles in a band of 8 m-tiles
-    const uint32_t band = L / band_sz, r = L % band_sz;
-    const uint32_t mrows = (band * 8 + 8 <= mt) ? 8 : (mt - band * 8);  // last band may be short
-    tile_n = r / mrows;
-    tile_m = band * 8 + r % mrows;
-  }
+  tile_of(L, g.M / TM, g.N / TN, tile_m, tile_n);
   const uint32_t m0 = tile_m * TM, n0 = tile_n * TN;
 
   // ---- global -> register staging: 8 + 8 sixteen-byte chunks per thread ----

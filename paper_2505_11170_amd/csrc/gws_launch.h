@@ -68,11 +68,16 @@ struct GemmArgs {
   float* scale;        // may be NULL
   uint16_t* w_hat;     // may be NULL
   uint32_t row0, cg0, seed_lo, seed_hi, step_lo, step_hi;
+  float* dbt;          // weight-gradient GEMM only: dL/db_t per block (with scale as input)
 };
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
 bool linear256_fused_applicable(const GemmArgs& g);
 int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream);
+// Weight-gradient GEMM (gws_gemm256_tn.hip): y[M x N] = x^T * w with x [K x M], w [K x N]
+// row-major (K = the contraction length); with_dbt adds Eq. 4's block reduction on y.
+bool gemm256_tn_applicable(const GemmArgs& g);
+int launch_gemm256_tn(const GemmArgs& g, bool with_dbt, hipStream_t stream);
 
 }  // namespace gws

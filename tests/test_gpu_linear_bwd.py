@@ -1,0 +1,107 @@
+"""GPU parity of gws_linear_bwd_w: the weight-gradient GEMM dW = X^T dY with the block reduction of the
+paper's Eq. 4 in its epilogue.  dW is checked against the fp64 oracle GEMM (one BF16 rounding + fp32
+accumulation in any order); dL/db_t is checked against the oracle's backward pass on the very dW bytes
+the GPU produced (the reduction is defined on the rounded BF16 gradient), to the 1e-5 bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_11170_amd as gws
+from paper_2505_11170_amd import synth
+from gpu_util import DEV, assert_dbt_close, ensure_built
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def f64(bits):
+    return (np.ascontiguousarray(bits).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def run_case(M, K, N, w_is_nk, idx, step=4, rows_sel=None, pad=0, row0=0, col0=0):
+    x = synth.make_activation(idx, M, K)
+    dy = (synth.make_activation(idx + 1, M, N).float() * 1e-3).to(torch.bfloat16)   # upstream gradient ~ N(0, 1e-3)
+    rows, cols = (N, K) if w_is_nk else (K, N)
+    ld = cols + pad
+    nbr, nbc = rows // 32, cols // 32
+    gen = torch.Generator().manual_seed(9000 + idx)
+    scale = (torch.rand(nbr, nbc, generator=gen) * 1e-3 + 1e-5).float()
+    seed = oracle.derive_seed(2, idx)
+    dw = torch.zeros(rows, ld, dtype=torch.bfloat16, device=DEV)
+    dbt = torch.full((nbr, nbc), float("nan"), device=DEV)
+    d = gws.TensorDesc(rows=rows, cols=cols, seed=seed, scale=scale.to(DEV), dw=dw, dbt=dbt, ld=ld, row0=row0, col0=col0)
+    xg, dyg = x.to(DEV), dy.to(DEV)
+    gws.gws_linear_bwd_w(xg, dyg, d, step, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    dw_bits = synth.bits(dw)
+    assert (dw_bits[:, cols:] == 0).all()                       # padding columns are never written
+    # dW against the fp64 GEMM: rows of dW are columns of A (X, or dY for the [N x K] layout)
+    a, b = (dy, x) if w_is_nk else (x, dy)
+    at = np.ascontiguousarray(synth.bits(a).T)
+    sel = None if rows_sel is None else np.asarray(rows_sel)
+    y64, yabs, _ = oracle.linear_fwd(at, synth.bits(b), rows_sel=sel)
+    got = f64(dw_bits[:, :cols] if sel is None else dw_bits[sel, :cols])
+    tol = 2.0 ** -8 * np.abs(y64) + M * 2.0 ** -24 * yabs + 1e-30
+    assert (np.abs(got - y64) <= tol).all(), ("dW", M, K, N, w_is_nk)
+    # dL/db_t against the oracle's Eq. 4 on the GPU's own dW bytes
+    _, ref_dbt, asum = oracle.sample_bwd(np.ascontiguousarray(dw_bits), scale.numpy(), seed, step, cols=cols, row0=row0, col0=col0)
+    assert_dbt_close(dbt.cpu().numpy(), ref_dbt, asum, ("dbt", M, K, N, w_is_nk))
+    return xg, dyg, d, dw_bits, dbt.cpu().numpy()
+
+
+@pytest.mark.parametrize("w_is_nk", [False, True])
+def test_single_tile_and_several_tiles(w_is_nk):
+    run_case(64, 256, 256, w_is_nk, 800)
+    run_case(192, 512, 768, w_is_nk, 802, pad=8)
+    run_case(128, 768, 256, w_is_nk, 804, row0=256, col0=512)     # a shard: the origin enters the noise counter
+
+
+@pytest.mark.parametrize("w_is_nk", [False, True])
+def test_config5_shape(w_is_nk):
+    M, K, N = 8192, 2048, 5632
+    rows = N if w_is_nk else K
+    run_case(M, K, N, w_is_nk, 810, rows_sel=[0, 1, 255, 256, rows // 2 + 3, rows - 1])
+
+
+def test_epilogue_agrees_with_the_separate_backward_kernel_and_plain_form():
+    xg, dyg, d, dw_bits, dbt = run_case(256, 512, 512, False, 820)
+    # the same dW without the reduction
+    dw2 = torch.zeros_like(d.dw)
+    d2 = gws.TensorDesc(rows=d.rows, cols=d.cols, seed=d.seed, dw=dw2, ld=d.ld)
+    gws.gws_linear_bwd_w(xg, dyg, d2, 4)
+    # and the separate kernel on those bytes
+    dbt3 = torch.zeros_like(d.dbt)
+    d3 = gws.TensorDesc(rows=d.rows, cols=d.cols, seed=d.seed, g=d.dw, dw=d.dw, dbt=dbt3, scale=d.scale, ld=d.ld)
+    gws.gws_sample_bwd([d3], 4)
+    torch.cuda.synchronize()
+    assert (synth.bits(dw2) == dw_bits).all()
+    a, b = dbt3.cpu().numpy().astype(np.float64), dbt.astype(np.float64)
+    _, _, asum = oracle.sample_bwd(np.ascontiguousarray(dw_bits), d.scale.cpu().numpy(), d.seed, 4)
+    assert (np.abs(a - b) <= 1e-5 * np.abs(a) + 2e-6 * asum).all()
+
+
+def test_shape_and_argument_errors():
+    x = torch.zeros(64, 256, dtype=torch.bfloat16, device=DEV)
+    dy = torch.zeros(64, 256, dtype=torch.bfloat16, device=DEV)
+    dw = torch.zeros(256, 256, dtype=torch.bfloat16, device=DEV)
+    sc = torch.ones(8, 8, device=DEV)
+    ok = gws.TensorDesc(rows=256, cols=256, seed=1, dw=dw, dbt=torch.zeros(8, 8, device=DEV), scale=sc)
+    gws.gws_linear_bwd_w(x, dy, ok, 0)
+    for bad, status in [(gws.TensorDesc(rows=128, cols=256, seed=1, dw=dw), 2),            # rows not a multiple of 256
+                        (gws.TensorDesc(rows=256, cols=256, seed=1, dw=None), 1),
+                        (gws.TensorDesc(rows=256, cols=256, seed=1, dw=dw, dbt=sc), 1)]:   # dbt without scale
+        with pytest.raises(gws.GwsError) as e:
+            gws.gws_linear_bwd_w(x, dy, bad, 0)
+        assert e.value.status == status
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_bwd_w(x[:32], dy[:32], ok, 0)                                       # M not a multiple of 64
+    assert e.value.status == 2
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_bwd_w(x, dy, gws.TensorDesc(rows=256, cols=256, seed=1, dw=x), 0)   # dW on top of X
+    assert e.value.status == 6
+    torch.cuda.synchronize()
