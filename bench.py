@@ -210,6 +210,55 @@ def main():
                          "no params/s or GB/s figure exists for this path",
     }
     out["roofline"]["traffic"] = MEASURED_FWD_TRAFFIC_BYTES.get(args.workload)
+    # the same bytes moved by a kernel with the forward pass's launch shape, loads and stores and no
+    # arithmetic: the ceiling the memory system sets for this access pattern, timed the same way
+    def copy_call():
+        copy_call.k += 1
+        gws.gws_copy_tiles(res["sets"][copy_call.k % n_sets][1])
+    copy_call.k = 0
+    for _ in range(20):
+        copy_call()
+    cms = []
+    for _ in range(25):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        copy_call()
+        e1.record()
+        for _ in range(3):
+            copy_call()
+        cms.append((e0, e1))
+    torch.cuda.synchronize()
+    copy_ms = max(sum(a.elapsed_time(b) for a, b in cms) / len(cms) - pair_ms, 1e-6) / res["n_launch"]
+    copy_gbps = (FWD_BYTES_PER_PARAM * params / res["n_launch"]) / (copy_ms * 1e-3) / 1e9   # 2 B read + 2 B written
+    # and the backward pass's ceiling: a kernel of its launch shape that reads the same gradient buffers
+    # once and writes 4 bytes per block (the block maximum)
+    absmax_sets = [gws.pack([gws.TensorDesc(rows=d.rows, cols=d.cols, seed=0, w=d.g, scale=d.dbt) for d in descs])
+                   for descs, _ in res["sets"]]
+
+    def read_call():
+        read_call.k += 1
+        gws.gws_block_absmax(absmax_sets[read_call.k % n_sets])
+    read_call.k = 0
+    for _ in range(20):
+        read_call()
+    rms = []
+    for _ in range(25):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        read_call()
+        e1.record()
+        for _ in range(3):
+            read_call()
+        rms.append((e0, e1))
+    torch.cuda.synchronize()
+    read_ms = max(sum(a.elapsed_time(b) for a, b in rms) / len(rms) - pair_ms, 1e-6) / res["n_launch"]
+    read_gbps = ((2.0 * params + 4.0 * res["blocks"]) / res["n_launch"]) / (read_ms * 1e-3) / 1e9
+    out["roofline"]["bwd"]["read_same_pattern"] = {"kernel": "block_absmax_kernel", "launch_ms": read_ms,
+                                                   "GBps": read_gbps, "frac_of_hbm_peak": read_gbps / HBM_PEAK_GBS,
+                                                   "bwd_frac_of_this_ceiling": bwd_achieved / read_gbps}
+    out["roofline"]["copy_same_pattern"] = {"kernel": "copy_tiles_kernel", "launch_ms": copy_ms, "GBps": copy_gbps,
+                                            "frac_of_hbm_peak": copy_gbps / HBM_PEAK_GBS,
+                                            "fwd_frac_of_this_ceiling": achieved / copy_gbps}
     # ---- cpu_baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     if not args.no_cpu:
         import numpy as np

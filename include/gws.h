@@ -197,6 +197,18 @@ int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx,
                   const void* w, int64_t N, int64_t ldw, int w_is_nk,
                   void* y, int64_t ldy, void* stream);
 
+/* Measurement aid: copies w to w_hat for n tensors with the launch shape, loads and
+ * stores of gws_sample_fwd and none of its arithmetic.  Its rate is the ceiling the
+ * memory system sets for that access pattern, against which the forward pass is read.
+ * Uses fields w, w_hat, rows, cols, ld.                                              */
+int gws_copy_tiles(const gws_tensor* t, int n, void* stream);
+
+/* Step one of Eq. 3 alone: writes max_{b_l}|w| (exact, as fp32) of every 32x32 block into
+ * `scale`, for n tensors, with the launch shape and loads of gws_sample_bwd.  It reads
+ * each element once and writes 4 bytes per block, so its rate is the ceiling the memory
+ * system sets for the backward pass.  Uses fields w, scale, rows, cols, ld.            */
+int gws_block_absmax(const gws_tensor* t, int n, void* stream);
+
 /* The packed noise alone (paper Sec. 3.4: sign-magnitude, 4 bits per element,
  * 8 elements per 32-bit word): out is device u32 [rows x ceil(cols/8)], element
  * k of a group in bits 4k..4k+3, code = sign<<3 | |R|.  The training path never

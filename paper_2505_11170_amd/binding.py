@@ -17,7 +17,7 @@ _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_bwd_w",
-           "gws_gemm_bf16", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
+           "gws_gemm_bf16", "gws_copy_tiles", "gws_block_absmax", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
 
 
 class GwsError(RuntimeError):
@@ -110,6 +110,10 @@ def load_library() -> ctypes.CDLL:
     L.gws_sample_fwd_mx.restype = ci
     L.gws_linear_fwd.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
     L.gws_linear_fwd.restype = ci
+    L.gws_copy_tiles.argtypes = [tp, ci, vp]
+    L.gws_copy_tiles.restype = ci
+    L.gws_block_absmax.argtypes = [tp, ci, vp]
+    L.gws_block_absmax.restype = ci
     L.gws_linear_bwd_w.argtypes = [vp, vp, i64, i64, i64, tp, ci, u64, vp]
     L.gws_linear_bwd_w.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
@@ -292,6 +296,20 @@ def gws_gemm_bf16(x, w, y, w_is_nk: bool = False, stream=None) -> None:
     N = int(w.shape[0] if w_is_nk else w.shape[1])
     _check(L.gws_gemm_bf16(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
                            _p(y), int(y.stride(0)), _stream(stream)), "gws_gemm_bf16")
+
+
+def gws_copy_tiles(t: Sequence[TensorDesc], stream=None) -> None:
+    """Copy ``w`` to ``w_hat`` with the forward pass's access pattern (a measurement aid)."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_copy_tiles(arr, n, _stream(stream)), "gws_copy_tiles")
+
+
+def gws_block_absmax(t: Sequence[TensorDesc], stream=None) -> None:
+    """``scale`` := max|w| per 32x32 block (step one of paper Eq. 3; also the read-only ceiling measurement)."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_block_absmax(arr, n, _stream(stream)), "gws_block_absmax")
 
 
 def gws_noise_packed(out, rows: int, cols: int, seed: int, step: int, row0: int = 0, col0: int = 0,

@@ -78,6 +78,9 @@ inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
   return ((nbr + per_wg - 1) / per_wg) * (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
 }
 
+constexpr int kCopyOnly = -1;    // run_batched "format": the forward launch shape, copy kernel
+constexpr int kAbsmaxOnly = -2;  // the backward launch shape, block-maximum kernel (descriptor: w, scale)
+
 // Pack descriptors into as few launches as the kernel-argument segment and the
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 // `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
@@ -103,8 +106,10 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   uint64_t wgs = 0;
   auto flush = [&]() -> int {
     if (a.n == 0) return GWS_OK;
-    int rc = fwd ? launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, stream)
-                 : launch_sample_bwd(a, (uint32_t)wgs, stream);
+    int rc = (!fwd && fmt == kAbsmaxOnly) ? launch_block_absmax(a, (uint32_t)wgs, stream)
+             : !fwd ? launch_sample_bwd(a, (uint32_t)wgs, stream)
+             : fmt == kCopyOnly ? launch_copy_tiles(a, (uint32_t)wgs, stream)
+                                : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, stream);
     a.n = 0;
     wgs = 0;
     for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
@@ -122,6 +127,8 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
     TileDesc& d = a.t[a.n++];
     if (fwd) {
       d.p0 = t[i].w; d.p1 = t[i].w_hat; d.p2 = (void*)t[i].bt; d.p3 = t[i].scale;
+    } else if (fmt == kAbsmaxOnly) {
+      d.p0 = t[i].w; d.p1 = nullptr; d.p2 = nullptr; d.p3 = t[i].scale;
     } else {
       d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
     }
@@ -176,6 +183,35 @@ int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
     if (rc != GWS_OK) return rc;
   }
   return run_batched(t, n, nullptr, nullptr, false, 0, step, (hipStream_t)stream);
+}
+
+int gws_copy_tiles(const gws_tensor* t, int n, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_shape(t[i]);
+    if (rc != GWS_OK) return rc;
+    if (t[i].rows == 0 || t[i].cols == 0) continue;
+    if (!t[i].w || !t[i].w_hat) return GWS_ERR_NULL;
+    if (!aligned(t[i].w, 16) || !aligned(t[i].w_hat, 16)) return GWS_ERR_ALIGN;
+    if (overlap(t[i].w, t[i].w_hat, (size_t)t[i].rows * t[i].ld * 2)) return GWS_ERR_ALIAS;
+  }
+  return run_batched(t, n, nullptr, nullptr, true, kCopyOnly, 0, (hipStream_t)stream);
+}
+
+int gws_block_absmax(const gws_tensor* t, int n, void* stream) {
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_shape(t[i]);
+    if (rc != GWS_OK) return rc;
+    if (t[i].rows == 0 || t[i].cols == 0) continue;
+    if (!t[i].w || !t[i].scale) return GWS_ERR_NULL;
+    if (!aligned(t[i].w, 16) || !aligned(t[i].scale, 4)) return GWS_ERR_ALIGN;
+  }
+  return run_batched(t, n, nullptr, nullptr, false, kAbsmaxOnly, 0, (hipStream_t)stream);
 }
 
 int gws_sample_fwd_bi(const gws_tensor* t, int n, const gws_bitwidth* bw, int fmt, uint64_t step, void* stream) {

@@ -333,19 +333,27 @@ __device__ __forceinline__ MxCodes sample_group_mx_fp8(const u32x4 w, const Nois
 
 // sum over one group of g .* (2R), two elements per v_dot2 (products exact, fp32
 // accumulation).  2R in {0, +-2, +-4} has the BF16 patterns sign<<15 | nz<<14 |
-// m2<<7, three single-bit deposits per element.
+// m2<<7.  The three bits of every element are first moved to the top of a byte
+// (bits 7, 6 of a "high" byte: sign, nz; bit 7 of a "low" byte: m2), separately for
+// the elements in even and in odd nibbles; one byte permute then assembles the
+// pattern pair of register d from the bytes of nibbles d and d + 4.
 __device__ __forceinline__ float dot_group_2r(const u32x4 g, const Noise& n, float acc) {
-  const uint32_t u = (n.x3 & 0x88888888u) | (n.nz << 2);  // per nibble: bit 3 sign, bit 2 nz
-  const uint32_t v = n.m2 << 3;                            // per nibble: bit 3 m2
+  const uint32_t a = (n.x3 & 0x88888888u) | (n.nz << 2);   // per nibble: bit 3 sign, bit 2 nz
+  const uint32_t hi_odd = a & 0xC0C0C0C0u;                  // byte i: element of nibble 2i + 1
+  const uint32_t hi_even = (a << 4) & 0xC0C0C0C0u;          // byte i: element of nibble 2i
+  const uint32_t lo_odd = (n.m2 << 3) & 0x80808080u;
+  const uint32_t lo_even = (n.m2 << 7) & 0x80808080u;
+  // v_perm_b32 selectors: result bytes (lo, hi, lo, hi) from byte j and j + 2 of the two words
+  const uint32_t pat[4] = {__builtin_amdgcn_perm(hi_even, lo_even, 0x06020400u),   // nibbles 0, 4
+                           __builtin_amdgcn_perm(hi_odd, lo_odd, 0x06020400u),     // nibbles 1, 5
+                           __builtin_amdgcn_perm(hi_even, lo_even, 0x07030501u),   // nibbles 2, 6
+                           __builtin_amdgcn_perm(hi_odd, lo_odd, 0x07030501u)};    // nibbles 3, 7
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    const uint32_t hi2 = (u << (12 - 4 * d)) & 0xC000C000u;
-    const uint32_t m2b = (d <= 1 ? (v << (4 - 4 * d)) : (v >> (4 * d - 4))) & 0x00800080u;
-    const uint32_t pat = hi2 | m2b;
     const uint32_t gd = g[d];
     bf16x2 gv, rv;
     __builtin_memcpy(&gv, &gd, 4);
-    __builtin_memcpy(&rv, &pat, 4);
+    __builtin_memcpy(&rv, &pat[d], 4);
     acc = __builtin_amdgcn_fdot2_f32_bf16(gv, rv, acc, false);
   }
   return acc;

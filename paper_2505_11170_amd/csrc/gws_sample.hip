@@ -150,6 +150,67 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a
   }
 }
 
+// The forward kernel's memory traffic without its arithmetic: every tile is loaded and
+// stored back unchanged, same workgroup shape, same loads and stores.  What this kernel
+// reaches is the ceiling the memory system sets for the access pattern.
+__global__ __launch_bounds__(kThreads) void copy_tiles_kernel(const LaunchArgs a) {
+  int ti;
+  uint32_t byg, bx;
+  locate(a, ti, byg, bx);
+  const TileDesc& d = a.t[ti];
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t col_base = bx * kTileCols + wave * 64;
+  if (col_base >= d.cols) return;
+  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
+  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
+  uint16_t* __restrict__ dst = (uint16_t*)d.p1;
+  const uint32_t nbr = (d.rows + 31) >> 5;
+  const uint32_t by0 = byg * a.tiles_per_wg;
+  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
+  for (uint32_t by = by0; by < by_end; ++by) {
+    const Tile t = load_tile(src, d, by, col_base, col, r0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (t.nv[i] == 0) continue;
+      uint16_t* p = dst + (size_t)(by * 32 + r0 + 8 * i) * d.ld + col;
+      if (t.nv[i] == 8) store16(p, t.v[i]);
+      else store_partial(p, t.v[i], t.nv[i]);
+    }
+  }
+}
+
+// Step one of the forward pass alone: a = max|w| per 32x32 block (exact), written as fp32.
+// Reads every element once and writes 4 bytes per block, the traffic profile of the backward
+// pass: its rate is the ceiling the memory system sets for a read-only pass of this shape.
+__global__ __launch_bounds__(kThreads) void block_absmax_kernel(const LaunchArgs a) {
+  int ti;
+  uint32_t byg, bx;
+  locate(a, ti, byg, bx);
+  const TileDesc& d = a.t[ti];
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t col_base = bx * kTileCols + wave * 64;
+  if (col_base >= d.cols) return;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const uint32_t col = col_base + gc * 8;
+  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
+  float* __restrict__ out = (float*)d.p3;
+  const uint32_t nbr = (d.rows + 31) >> 5, nbc = (d.cols + 31) >> 5;
+  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
+  const uint32_t by0 = byg * a.tiles_per_wg;
+  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
+  Tile t = load_tile(src, d, by0, col_base, col, r0);
+  for (uint32_t by = by0;;) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m = absmax_pk(t.nv[i] < 8 ? mask_group(t.v[i], t.nv[i]) : t.v[i], m);
+    m = max(m & 0xFFFFu, m >> 16);
+    const uint32_t a16 = block_max_u32(m);
+    if (bcol < nbc && (gc & 3) == 0 && r0 == 0) out[(size_t)by * nbc + bcol] = __uint_as_float(a16 << 16);
+    if (++by >= by_end) break;
+    t = load_tile(src, d, by, col_base, col, r0);
+  }
+}
+
 __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict__ out, uint32_t rows,
                                                            uint32_t ngrp, uint32_t row0, uint32_t cg0,
                                                            uint32_t seed_lo, uint32_t seed_hi,
@@ -179,6 +240,18 @@ int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, hipS
     case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL(sample_fwd_kernel<2>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
     default: return GWS_ERR_FORMAT;
   }
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+int launch_copy_tiles(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
+  hipLaunchKernelGGL(copy_tiles_kernel, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+int launch_block_absmax(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
+  hipLaunchKernelGGL(block_absmax_kernel, dim3(n_wg), dim3(kThreads), 0, stream, a);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 

@@ -208,3 +208,47 @@ def test_config2_gpt2_124m_all_linears_fwd_bwd_3_steps():
             it["scale"] = s
         needed += check_backward(items, step)
     print(f"config 2: blocks needing the cancellation term of the db_t tolerance: {needed} of {3 * 82944}")
+
+
+def test_copy_tiles_moves_exactly_the_tensor():
+    # the measurement aid shares the forward pass's launch shape: every element copied once, padding untouched
+    shapes = [(768, 768), (40, 50), (33, 257), (0, 64), (96, 320)]
+    descs, keep = [], []
+    for i, (r, c) in enumerate(shapes):
+        ld = (c + 7) // 8 * 8 + 8
+        t = synth.make_tensor(900 + i, r, c, ld=ld, with_grad=False)
+        w = t["w"].to(DEV)
+        out = torch.full_like(w, 7.0)
+        descs.append(gws.TensorDesc(rows=r, cols=c, seed=0, w=w, w_hat=out, ld=ld))
+        keep.append((w, out, c))
+    gws.gws_copy_tiles(descs)
+    torch.cuda.synchronize()
+    for w, out, c in keep:
+        assert torch.equal(out[:, :c].view(torch.int16), w[:, :c].view(torch.int16))
+        assert (out[:, c:] == 7.0).all()
+
+
+def test_block_absmax_is_exact():
+    shapes = [(768, 768), (40, 50), (33, 257), (0, 64), (96, 320), (1, 1)]
+    descs, keep = [], []
+    for i, (r, c) in enumerate(shapes):
+        ld = (c + 7) // 8 * 8 + 8
+        t = synth.make_tensor(920 + i, r, c, ld=ld, with_grad=False)
+        w = t["w"].clone()
+        w[:, c:] = 1.0e30                                   # padding must not enter the maximum
+        if r >= 33 and c >= 40:
+            w[32, 39] = -3.0                                # a negative maximum, in an edge position of its block
+        nbr, nbc = synth.n_blocks(r, c)
+        out = torch.full((nbr, nbc), float("nan"), device=DEV)
+        descs.append(gws.TensorDesc(rows=r, cols=c, seed=0, w=w.to(DEV), scale=out, ld=ld))
+        keep.append((w, out, r, c))
+    gws.gws_block_absmax(descs)
+    torch.cuda.synchronize()
+    for w, out, r, c in keep:
+        if r == 0 or c == 0:
+            continue
+        wv = w[:, :c].float().abs().numpy()
+        nbr, nbc = synth.n_blocks(r, c)
+        ref = np.array([[wv[bi * 32:bi * 32 + 32, bj * 32:bj * 32 + 32].max() for bj in range(nbc)] for bi in range(nbr)],
+                       dtype=np.float32)
+        assert np.array_equal(out.cpu().numpy(), ref), (r, c)
