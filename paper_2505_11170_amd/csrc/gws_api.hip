@@ -61,7 +61,7 @@ int check_bwd(const gws_tensor& t) {
   return GWS_OK;
 }
 
-void fill_common(TileDesc& d, const gws_tensor& t) {
+void fill_common(TileDesc& d, const gws_tensor& t, uint32_t per_x) {
   d.rows = (uint32_t)t.rows;
   d.cols = (uint32_t)t.cols;
   d.ld = (uint32_t)t.ld;
@@ -69,13 +69,14 @@ void fill_common(TileDesc& d, const gws_tensor& t) {
   d.cg0 = (uint32_t)(t.col0 / 8);
   d.seed_lo = (uint32_t)t.seed;
   d.seed_hi = (uint32_t)(t.seed >> 32);
-  d.tiles_x = (uint32_t)((t.cols + kTileCols - 1) / kTileCols);
+  d.tiles_x = (uint32_t)(((t.cols + kTileCols - 1) / kTileCols + per_x - 1) / per_x);
 }
 
-// Workgroups a tensor needs when each walks down `per_wg` block rows of a 256-column strip.
-inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg) {
+// Workgroups a tensor needs when each covers `per_wg` block rows by `per_x` 256-column tiles.
+inline uint64_t wg_count(const gws_tensor& t, uint32_t per_wg, uint32_t per_x) {
   const uint64_t nbr = (uint64_t)((t.rows + 31) / 32);
-  return ((nbr + per_wg - 1) / per_wg) * (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
+  const uint64_t ntx = (uint64_t)((t.cols + kTileCols - 1) / kTileCols);
+  return ((nbr + per_wg - 1) / per_wg) * ((ntx + per_x - 1) / per_x);
 }
 
 constexpr int kCopyOnly = -1;    // run_batched "format": the forward launch shape, copy kernel
@@ -87,21 +88,24 @@ constexpr int kAbsmaxOnly = -2;  // the backward launch shape, block-maximum ker
 // `mx` (one per tensor, forward only) switches the output to MX element codes and block scales.
 int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx_out* mx, bool fwd, int fmt,
                 uint64_t step, hipStream_t stream) {
-  // Block rows per workgroup.  Forward: 1 (most workgroups, fewest registers).  Backward
-  // does less per tile, so a workgroup takes up to 8 while at least ~20 workgroups per
-  // compute unit remain to balance the 256 units.
+  // Tiles per workgroup.  Forward: one (most workgroups, fewest registers; measured best).
+  // Backward does less per tile, so the per-wavefront set-up shows: a workgroup takes up to
+  // four neighbouring column tiles while at least ~3000 workgroups (12 per compute unit)
+  // remain.  Neighbouring column tiles, not rows: the workgroups in flight then still cover
+  // a contiguous stretch of memory, which the memory system rewards.
   uint64_t total = 0;
   for (int i = 0; i < n; ++i)
-    if (t[i].rows > 0 && t[i].cols > 0) total += wg_count(t[i], 1);
-  uint32_t per_wg = 1;
+    if (t[i].rows > 0 && t[i].cols > 0) total += wg_count(t[i], 1, 1);
+  uint32_t per_wg = 1, per_x = 1;
   if (!fwd)
-    while (per_wg < 8 && total / (2 * per_wg) >= 5000) per_wg *= 2;
+    while (per_x < 4 && total / (per_x + 1) >= 3000) ++per_x;
 
   LaunchArgs a;
   memset(&a, 0, sizeof a);
   a.step_lo = (uint32_t)step;
   a.step_hi = (uint32_t)(step >> 32);
   a.tiles_per_wg = per_wg;
+  a.tiles_per_wg_x = per_x;
   for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
   uint64_t wgs = 0;
   auto flush = [&]() -> int {
@@ -117,7 +121,7 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   };
   for (int i = 0; i < n; ++i) {
     if (t[i].rows == 0 || t[i].cols == 0) continue;
-    const uint64_t wc = wg_count(t[i], per_wg);
+    const uint64_t wc = wg_count(t[i], per_wg, per_x);
     if (wc >= 0x7FFFFFF0ull) return GWS_ERR_SHAPE;
     if (a.n == (uint32_t)kMaxTensorsPerLaunch || wgs + wc >= 0x7FFFFFF0ull) {
       int rc = flush();
@@ -125,6 +129,7 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
     }
     a.tile_begin[a.n] = (uint32_t)wgs;
     TileDesc& d = a.t[a.n++];
+    d.first_wg = (uint32_t)wgs;
     if (fwd) {
       d.p0 = t[i].w; d.p1 = t[i].w_hat; d.p2 = (void*)t[i].bt; d.p3 = t[i].scale;
     } else if (fmt == kAbsmaxOnly) {
@@ -132,7 +137,7 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
     } else {
       d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
     }
-    fill_common(d, t[i]);
+    fill_common(d, t[i], per_x);
     d.p4 = nullptr;
     d.b_target = 0.0f;
     d.b_delta = 1.0f;

@@ -30,14 +30,16 @@ struct TileDesc {
   uint32_t rows, cols, ld;
   uint32_t row0, cg0;          // shard origin: row offset, column-group (col0 / 8) offset
   uint32_t seed_lo, seed_hi;
-  uint32_t tiles_x;            // workgroup tiles per block row = ceil(cols / 256)
+  uint32_t tiles_x;            // workgroups per row of workgroups = ceil(ceil(cols / 256) / tiles_per_wg_x)
   float b_target, b_delta;     // Eq. 11: b_delta = b_init - b_target
   float lambda_m;              // Eq. 12: lambda / (blocks of the layer); backward only
   uint32_t ldc;                // MX output: bytes per row of element codes
+  uint32_t first_wg;           // this tensor's first workgroup within the launch (= its tile_begin entry)
+  uint32_t reserved;
 };
-static_assert(sizeof(TileDesc) == 88, "descriptor layout");
+static_assert(sizeof(TileDesc) == 96, "descriptor layout");
 
-// Passed by value: lives in the kernel-argument segment (about 5 KiB; the segment
+// Passed by value: lives in the kernel-argument segment (about 5.5 KiB; the segment
 // of a gfx950 code object is not limited to 4 KiB).
 struct LaunchArgs {
   // First workgroup of every tensor within the launch; entries past n hold 0x7FFFFFFF.
@@ -47,7 +49,8 @@ struct LaunchArgs {
   TileDesc t[kMaxTensorsPerLaunch];
   uint32_t n;
   uint32_t step_lo, step_hi;
-  uint32_t tiles_per_wg;       // consecutive block rows one workgroup walks down (>= 1)
+  uint32_t tiles_per_wg;       // consecutive block rows one workgroup covers (>= 1)
+  uint32_t tiles_per_wg_x;     // neighbouring 256-column tiles one workgroup covers (>= 1)
 };
 static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the size verified on the device");
 

@@ -24,45 +24,91 @@
 
 namespace gws {
 
-// Which tensor, which block-row group and which column strip this workgroup owns.
-// Pure scalar arithmetic: tile_begin[] ascends, unused entries are 0x7FFFFFFF, so
-// (wg - tile_begin[i]) has its top bit clear exactly for the tensors that start
-// at or before wg.
-__device__ __forceinline__ void locate(const LaunchArgs& a, int& ti, uint32_t& byg, uint32_t& bx) {
+// Which tensor, which block-row group and which column strip this workgroup owns, and that
+// tensor's descriptor.  Pure scalar work: tile_begin[] ascends, unused entries are
+// 0x7FFFFFFF, so (wg - tile_begin[i]) has its top bit clear exactly for the tensors that
+// start at or before wg.
+// A wavefront lives for one tile, so what it waits for before its first global load counts:
+// the prefix table is fetched with four wide scalar loads issued together, the descriptor
+// with three, i.e. two scalar-cache round trips in all.  (Left to itself the compiler
+// fetches the table in three dependent steps and the descriptor field by field, as each is
+// first used: six to nine round trips.)  The empty asm statements pin the loaded values in
+// scalar registers at that point, which makes the loads of a batch issue back to back.
+typedef uint32_t u32x16s __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x8s __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2s __attribute__((ext_vector_type(2)));
+static_assert(kMaxTensorsPerLaunch == 56 && sizeof(TileDesc) == 96, "locate() is laid out for this table");
+
+__device__ __forceinline__ TileDesc locate(const LaunchArgs& a, uint32_t& byg, uint32_t& bx) {
   const uint32_t wg = blockIdx.x;
+  const uint32_t* tb = a.tile_begin;
+  u32x16s t0 = *(const u32x16s*)(tb), t1 = *(const u32x16s*)(tb + 16), t2 = *(const u32x16s*)(tb + 32);
+  u32x8s t3 = *(const u32x8s*)(tb + 48);
+  asm volatile("" : "+s"(t0), "+s"(t1), "+s"(t2), "+s"(t3));
   uint32_t after = 0;
 #pragma unroll
-  for (int i = 0; i < kMaxTensorsPerLaunch; ++i) after += (wg - a.tile_begin[i]) >> 31;
-  ti = kMaxTensorsPerLaunch - 1 - (int)after;
-  const uint32_t local = wg - a.tile_begin[ti];
-  byg = local / a.t[ti].tiles_x;
-  bx = local - byg * a.t[ti].tiles_x;
+  for (int i = 0; i < 16; ++i) after += ((wg - t0[i]) >> 31) + ((wg - t1[i]) >> 31) + ((wg - t2[i]) >> 31);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) after += (wg - t3[i]) >> 31;
+  const uint32_t ti = kMaxTensorsPerLaunch - 1 - after;
+
+  const uint32_t* dp = (const uint32_t*)&a.t[ti];
+  u32x16s d0 = *(const u32x16s*)(dp);
+  u32x8s d1 = *(const u32x8s*)(dp + 16);
+  asm volatile("" : "+s"(d0), "+s"(d1));
+  uint32_t w[24];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) w[i] = d0[i];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w[16 + i] = d1[i];
+  TileDesc d;
+  __builtin_memcpy(&d, w, sizeof d);
+
+  const uint32_t local = wg - d.first_wg;
+  byg = local / d.tiles_x;
+  bx = local - byg * d.tiles_x;
+  return d;
+}
+
+// The tiles of one workgroup: `tiles_per_wg_x` neighbouring column tiles by `tiles_per_wg`
+// block rows, column tiles first, so that the workgroups running at any moment cover a
+// contiguous stretch of the tensor.  Each wavefront handles its 64-column strip of every
+// tile; `body(by, col_base, tile)` is called for strips that exist.  The first tile is
+// loaded ahead of the loop, so the common one-tile case stays straight-line code.
+template <class F>
+__device__ __forceinline__ void walk_tiles(const LaunchArgs& a, const TileDesc& d, uint32_t byg, uint32_t bxg,
+                                           F&& body) {
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t r0 = lane >> 3, gcol = (lane & 7) * 8;
+  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
+  const uint32_t nbr = (d.rows + 31) >> 5, ntx = (d.cols + kTileCols - 1) / kTileCols;
+  const uint32_t by0 = byg * a.tiles_per_wg, by_end = min(by0 + a.tiles_per_wg, nbr);
+  const uint32_t bx0 = bxg * a.tiles_per_wg_x, bx_end = min(bx0 + a.tiles_per_wg_x, ntx);
+  uint32_t by = by0, bx = bx0;
+  uint32_t col_base = bx * kTileCols + wave * 64;
+  Tile t = load_tile(src, d, by, col_base, col_base + gcol, r0);
+  for (;;) {
+    if (col_base < d.cols) body(by, col_base, t);
+    if (++bx >= bx_end) {
+      bx = bx0;
+      if (++by >= by_end) break;
+    }
+    col_base = bx * kTileCols + wave * 64;
+    t = load_tile(src, d, by, col_base, col_base + gcol, r0);
+  }
 }
 
 // MX: write element codes and E8M0 block scales instead of the BF16 container.
 template <int FMT, bool MX = false>
 __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
-  int ti;
-  uint32_t byg, bx;
-  locate(a, ti, byg, bx);
-  const TileDesc& d = a.t[ti];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint32_t col_base = bx * kTileCols + wave * 64;
-  if (col_base >= d.cols) return;  // whole wavefront past the right edge
-  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
-  const uint16_t* __restrict__ w = (const uint16_t*)d.p0;
-  const uint32_t nbr = (d.rows + 31) >> 5;
-  const uint32_t by0 = byg * a.tiles_per_wg;
-  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
-
-  // first tile loaded ahead of the loop: the common one-tile case stays straight-line code
-  Tile t = load_tile(w, d, by0, col_base, col, r0);
-  for (uint32_t by = by0;;) {
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t lane = threadIdx.x & 63;
+  walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
     if (t.full) fwd_tile<FMT, true, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
     else fwd_tile<FMT, false, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
-    if (++by >= by_end) break;
-    t = load_tile(w, d, by, col_base, col, r0);
-  }
+  });
 }
 
 template <bool FULL, bool COPY>
@@ -122,22 +168,11 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
 }
 
 __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a) {
-  int ti;
-  uint32_t byg, bx;
-  locate(a, ti, byg, bx);
-  const TileDesc& d = a.t[ti];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint32_t col_base = bx * kTileCols + wave * 64;
-  if (col_base >= d.cols) return;
-  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
-  const uint16_t* __restrict__ g = (const uint16_t*)d.p0;
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t lane = threadIdx.x & 63;
   const bool copy = d.p1 != nullptr;  // NULL: the pass-through is an alias
-  const uint32_t nbr = (d.rows + 31) >> 5;
-  const uint32_t by0 = byg * a.tiles_per_wg;
-  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
-
-  Tile t = load_tile(g, d, by0, col_base, col, r0);
-  for (uint32_t by = by0;;) {
+  walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
     if (t.full) {
       if (copy) bwd_tile<true, true>(a, d, t, by, col_base, lane);
       else bwd_tile<true, false>(a, d, t, by, col_base, lane);
@@ -145,70 +180,47 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a
       if (copy) bwd_tile<false, true>(a, d, t, by, col_base, lane);
       else bwd_tile<false, false>(a, d, t, by, col_base, lane);
     }
-    if (++by >= by_end) break;
-    t = load_tile(g, d, by, col_base, col, r0);
-  }
+  });
 }
 
 // The forward kernel's memory traffic without its arithmetic: every tile is loaded and
 // stored back unchanged, same workgroup shape, same loads and stores.  What this kernel
 // reaches is the ceiling the memory system sets for the access pattern.
 __global__ __launch_bounds__(kThreads) void copy_tiles_kernel(const LaunchArgs a) {
-  int ti;
-  uint32_t byg, bx;
-  locate(a, ti, byg, bx);
-  const TileDesc& d = a.t[ti];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint32_t col_base = bx * kTileCols + wave * 64;
-  if (col_base >= d.cols) return;
-  const uint32_t col = col_base + (lane & 7) * 8, r0 = lane >> 3;
-  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t lane = threadIdx.x & 63;
   uint16_t* __restrict__ dst = (uint16_t*)d.p1;
-  const uint32_t nbr = (d.rows + 31) >> 5;
-  const uint32_t by0 = byg * a.tiles_per_wg;
-  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
-  for (uint32_t by = by0; by < by_end; ++by) {
-    const Tile t = load_tile(src, d, by, col_base, col, r0);
+  walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (t.nv[i] == 0) continue;
-      uint16_t* p = dst + (size_t)(by * 32 + r0 + 8 * i) * d.ld + col;
+      uint16_t* p = dst + (size_t)(by * 32 + (lane >> 3) + 8 * i) * d.ld + col_base + (lane & 7) * 8;
       if (t.nv[i] == 8) store16(p, t.v[i]);
       else store_partial(p, t.v[i], t.nv[i]);
     }
-  }
+  });
 }
 
 // Step one of the forward pass alone: a = max|w| per 32x32 block (exact), written as fp32.
 // Reads every element once and writes 4 bytes per block, the traffic profile of the backward
 // pass: its rate is the ceiling the memory system sets for a read-only pass of this shape.
 __global__ __launch_bounds__(kThreads) void block_absmax_kernel(const LaunchArgs a) {
-  int ti;
-  uint32_t byg, bx;
-  locate(a, ti, byg, bx);
-  const TileDesc& d = a.t[ti];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint32_t col_base = bx * kTileCols + wave * 64;
-  if (col_base >= d.cols) return;
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t lane = threadIdx.x & 63;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
-  const uint32_t col = col_base + gc * 8;
-  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
   float* __restrict__ out = (float*)d.p3;
-  const uint32_t nbr = (d.rows + 31) >> 5, nbc = (d.cols + 31) >> 5;
-  const uint32_t bcol = (col_base >> 5) + (gc >> 2);
-  const uint32_t by0 = byg * a.tiles_per_wg;
-  const uint32_t by_end = min(by0 + a.tiles_per_wg, nbr);
-  Tile t = load_tile(src, d, by0, col_base, col, r0);
-  for (uint32_t by = by0;;) {
+  const uint32_t nbc = (d.cols + 31) >> 5;
+  walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
     uint32_t m = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) m = absmax_pk(t.nv[i] < 8 ? mask_group(t.v[i], t.nv[i]) : t.v[i], m);
     m = max(m & 0xFFFFu, m >> 16);
     const uint32_t a16 = block_max_u32(m);
+    const uint32_t bcol = (col_base >> 5) + (gc >> 2);
     if (bcol < nbc && (gc & 3) == 0 && r0 == 0) out[(size_t)by * nbc + bcol] = __uint_as_float(a16 << 16);
-    if (++by >= by_end) break;
-    t = load_tile(src, d, by, col_base, col, r0);
-  }
+  });
 }
 
 __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict__ out, uint32_t rows,
