@@ -70,6 +70,8 @@ void fill_common(TileDesc& d, const gws_tensor& t, uint32_t per_x) {
   d.seed_lo = (uint32_t)t.seed;
   d.seed_hi = (uint32_t)(t.seed >> 32);
   d.tiles_x = (uint32_t)(((t.cols + kTileCols - 1) / kTileCols + per_x - 1) / per_x);
+  const uint64_t inv = ((uint64_t)1 << 32) / d.tiles_x;
+  d.tiles_x_inv = inv > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)inv;
 }
 
 // Workgroups a tensor needs when each covers `per_wg` block rows by `per_x` 256-column tiles.

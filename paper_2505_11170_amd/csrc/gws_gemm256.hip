@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs 
   TileDesc d;  // the stored weight as the forward pass describes it (cols is a multiple of 64 here)
   d.p0 = g.w; d.p1 = g.w_hat; d.p2 = (void*)g.bt; d.p3 = g.scale; d.p4 = nullptr;
   d.b_target = 0.0f; d.b_delta = 1.0f; d.lambda_m = 0.0f;  // g.bt holds b_t itself
-  d.ldc = 0; d.first_wg = 0; d.reserved = 0;
+  d.ldc = 0; d.first_wg = 0; d.tiles_x_inv = 0;
   d.rows = W_NK ? g.N : g.K; d.cols = W_NK ? g.K : g.N; d.ld = g.ldw;
   d.row0 = g.row0; d.cg0 = g.cg0; d.seed_lo = g.seed_lo; d.seed_hi = g.seed_hi; d.tiles_x = 0;
 

@@ -35,7 +35,7 @@ struct TileDesc {
   float lambda_m;              // Eq. 12: lambda / (blocks of the layer); backward only
   uint32_t ldc;                // MX output: bytes per row of element codes
   uint32_t first_wg;           // this tensor's first workgroup within the launch (= its tile_begin entry)
-  uint32_t reserved;
+  uint32_t tiles_x_inv;        // min(floor(2^32 / tiles_x), 2^32 - 1): division by multiplication in locate()
 };
 static_assert(sizeof(TileDesc) == 96, "descriptor layout");
 

@@ -65,9 +65,16 @@ __device__ __forceinline__ TileDesc locate(const LaunchArgs& a, uint32_t& byg, u
   TileDesc d;
   __builtin_memcpy(&d, w, sizeof d);
 
+  // local / tiles_x by the host's reciprocal: the estimate is at most one too small
   const uint32_t local = wg - d.first_wg;
-  byg = local / d.tiles_x;
-  bx = local - byg * d.tiles_x;
+  uint32_t q = __umulhi(local, d.tiles_x_inv);
+  uint32_t r = local - q * d.tiles_x;
+  if (r >= d.tiles_x) {
+    ++q;
+    r -= d.tiles_x;
+  }
+  byg = q;
+  bx = r;
   return d;
 }
 
