@@ -7,6 +7,14 @@
 
 namespace gws {
 
+// Pointers into global memory, typed as such: the accesses through them are global (not
+// flat) instructions whatever the pointer's provenance.
+#define GWS_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ GWS_GLOBAL T* global_ptr(const void* p) {
+  return (GWS_GLOBAL T*)(uintptr_t)p;
+}
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef short i16x2 __attribute__((ext_vector_type(2)));

@@ -224,7 +224,7 @@ __device__ __forceinline__ void sample_tiles(const GemmArgs& g, const TileDesc& 
       const uint32_t id = base + j * stride;
       if (id < ntiles) {
         const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
-        t[j] = load_tile((const uint16_t*)d.p0, d, by, cb, cb + gc * 8, r0);
+        t[j] = load_tile(global_ptr<uint16_t>(d.p0), d, by, cb, cb + gc * 8, r0);
       }
     }
 #pragma unroll

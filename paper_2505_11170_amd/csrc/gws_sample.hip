@@ -36,8 +36,6 @@ namespace gws {
 // scalar registers at that point, which makes the loads of a batch issue back to back.
 typedef uint32_t u32x16s __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x8s __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2s __attribute__((ext_vector_type(2)));
 static_assert(kMaxTensorsPerLaunch == 56 && sizeof(TileDesc) == 96, "locate() is laid out for this table");
 
 __device__ __forceinline__ TileDesc locate(const LaunchArgs& a, uint32_t& byg, uint32_t& bx) {
@@ -88,7 +86,7 @@ __device__ __forceinline__ void walk_tiles(const LaunchArgs& a, const TileDesc& 
                                            F&& body) {
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint32_t r0 = lane >> 3, gcol = (lane & 7) * 8;
-  const uint16_t* __restrict__ src = (const uint16_t*)d.p0;
+  const GWS_GLOBAL uint16_t* __restrict__ src = global_ptr<uint16_t>(d.p0);
   const uint32_t nbr = (d.rows + 31) >> 5, ntx = (d.cols + kTileCols - 1) / kTileCols;
   const uint32_t by0 = byg * a.tiles_per_wg, by_end = min(by0 + a.tiles_per_wg, nbr);
   const uint32_t bx0 = bxg * a.tiles_per_wg_x, bx_end = min(bx0 + a.tiles_per_wg_x, ntx);
@@ -124,9 +122,9 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   const uint32_t row_base = by * 32;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   const uint32_t col = col_base + gc * 8;
-  uint16_t* __restrict__ dw = (uint16_t*)d.p1;
-  float* __restrict__ dbt = (float*)d.p2;
-  const float* __restrict__ scale = (const float*)d.p3;
+  GWS_GLOBAL uint16_t* __restrict__ dw = global_ptr<uint16_t>(d.p1);
+  GWS_GLOBAL float* __restrict__ dbt = global_ptr<float>(d.p2);
+  const GWS_GLOBAL float* __restrict__ scale = global_ptr<float>(d.p3);
   const uint32_t cg = d.cg0 + (col >> 3);
 
   // the block's lane that writes the gradient fetches what it needs first, so the
@@ -138,7 +136,7 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   float s32 = 0.0f, bi = 0.0f;
   if (writer) {
     s32 = scale[blk];
-    if (d.p4 != nullptr) bi = ((const float*)d.p4)[blk];
+    if (d.p4 != nullptr) bi = global_ptr<float>(d.p4)[blk];
   }
 
   // sum_{b_l}(g .* R), accumulated as sum(g .* 2R) / 2: every product is exact
@@ -150,7 +148,7 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
     if (!FULL && t.nv[i] == 0) continue;
     const uint32_t row = row_base + r0 + 8 * i;
     if (COPY) {  // dL/dw = dL/dw_hat, bit for bit
-      uint16_t* dst = dw + (size_t)row * d.ld + col;
+      GWS_GLOBAL uint16_t* dst = dw + (size_t)row * d.ld + col;
       if (FULL || t.nv[i] == 8) store16(dst, t.v[i]);
       else store_partial(dst, t.v[i], t.nv[i]);
     }
@@ -197,12 +195,12 @@ __global__ __launch_bounds__(kThreads) void copy_tiles_kernel(const LaunchArgs a
   uint32_t byg, bxg;
   const TileDesc d = locate(a, byg, bxg);
   const uint32_t lane = threadIdx.x & 63;
-  uint16_t* __restrict__ dst = (uint16_t*)d.p1;
+  GWS_GLOBAL uint16_t* __restrict__ dst = global_ptr<uint16_t>(d.p1);
   walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (t.nv[i] == 0) continue;
-      uint16_t* p = dst + (size_t)(by * 32 + (lane >> 3) + 8 * i) * d.ld + col_base + (lane & 7) * 8;
+      GWS_GLOBAL uint16_t* p = dst + (size_t)(by * 32 + (lane >> 3) + 8 * i) * d.ld + col_base + (lane & 7) * 8;
       if (t.nv[i] == 8) store16(p, t.v[i]);
       else store_partial(p, t.v[i], t.nv[i]);
     }
@@ -217,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void block_absmax_kernel(const LaunchArgs
   const TileDesc d = locate(a, byg, bxg);
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
-  float* __restrict__ out = (float*)d.p3;
+  GWS_GLOBAL float* __restrict__ out = global_ptr<float>(d.p3);
   const uint32_t nbc = (d.cols + 31) >> 5;
   walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
     uint32_t m = 0;

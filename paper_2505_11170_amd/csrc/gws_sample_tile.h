@@ -15,11 +15,11 @@ __device__ __forceinline__ int valid_count(uint32_t row, uint32_t col, uint32_t 
   return left >= 8 ? 8 : (int)left;
 }
 
-__device__ __forceinline__ u32x4 load16(const uint16_t* p) {
-  return __builtin_nontemporal_load((const u32x4*)p);
+__device__ __forceinline__ u32x4 load16(const GWS_GLOBAL uint16_t* p) {
+  return __builtin_nontemporal_load((const GWS_GLOBAL u32x4*)p);
 }
-__device__ __forceinline__ void store16(uint16_t* p, const u32x4 v) {
-  __builtin_nontemporal_store(v, (u32x4*)p);
+__device__ __forceinline__ void store16(GWS_GLOBAL uint16_t* p, const u32x4 v) {
+  __builtin_nontemporal_store(v, (GWS_GLOBAL u32x4*)p);
 }
 
 // Zero the elements of a group that lie past the right edge (nv valid of 8).
@@ -30,7 +30,7 @@ __device__ __forceinline__ u32x4 mask_group(u32x4 v, int nv) {
   return v;
 }
 
-__device__ __forceinline__ void store_partial(uint16_t* dst, const u32x4 v, int nv) {
+__device__ __forceinline__ void store_partial(GWS_GLOBAL uint16_t* dst, const u32x4 v, int nv) {
 #pragma unroll
   for (int k = 0; k < 8; ++k)
     if (k < nv) dst[k] = (uint16_t)(v[k >> 1] >> ((k & 1) * 16));
@@ -44,7 +44,7 @@ struct Tile {
 };
 
 // A 16-byte load never leaves its row: ld % 8 == 0 and ld >= cols.
-__device__ __forceinline__ Tile load_tile(const uint16_t* __restrict__ src, const TileDesc& d, uint32_t by,
+__device__ __forceinline__ Tile load_tile(const GWS_GLOBAL uint16_t* __restrict__ src, const TileDesc& d, uint32_t by,
                                           uint32_t col_base, uint32_t col, uint32_t r0) {
   Tile t;
   const uint32_t row_base = by * 32;
@@ -71,21 +71,21 @@ __device__ __forceinline__ Tile load_tile(const uint16_t* __restrict__ src, cons
 // (col / 8) * 6, written as three 2-byte stores (a row of codes is only 2-byte aligned).
 // nv < 8: only the bytes that hold existing elements (unused bits of the last one are 0).
 template <int FMT>
-__device__ __forceinline__ void store_codes(uint8_t* row, uint32_t col, const MxCodes c, int nv) {
+__device__ __forceinline__ void store_codes(GWS_GLOBAL uint8_t* row, uint32_t col, const MxCodes c, int nv) {
   if (FMT == 1) {
-    uint8_t* dst = row + col;
+    GWS_GLOBAL uint8_t* dst = row + col;
     if (nv == 8) {
       typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-      __builtin_nontemporal_store(u32x2{c.lo, c.hi}, (u32x2*)dst);
+      __builtin_nontemporal_store(u32x2{c.lo, c.hi}, (GWS_GLOBAL u32x2*)dst);
     } else {
 #pragma unroll
       for (int k = 0; k < 8; ++k)
         if (k < nv) dst[k] = (uint8_t)((k < 4 ? c.lo : c.hi) >> (8 * (k & 3)));
     }
   } else {
-    uint8_t* dst = row + (col >> 3) * 6;
+    GWS_GLOBAL uint8_t* dst = row + (col >> 3) * 6;
     if (nv == 8) {
-      uint16_t* d16 = (uint16_t*)dst;
+      GWS_GLOBAL uint16_t* d16 = (GWS_GLOBAL uint16_t*)dst;
       __builtin_nontemporal_store((uint16_t)c.lo, d16);
       __builtin_nontemporal_store((uint16_t)(c.lo >> 16), d16 + 1);
       __builtin_nontemporal_store((uint16_t)c.hi, d16 + 2);
@@ -110,9 +110,9 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   const uint32_t row_base = by * 32;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   const uint32_t col = col_base + gc * 8;
-  uint16_t* __restrict__ w_hat = (uint16_t*)d.p1;
-  const float* __restrict__ bt = (const float*)d.p2;
-  float* __restrict__ scale = (float*)d.p3;
+  GWS_GLOBAL uint16_t* __restrict__ w_hat = global_ptr<uint16_t>(d.p1);
+  const GWS_GLOBAL float* __restrict__ bt = global_ptr<float>(d.p2);
+  GWS_GLOBAL float* __restrict__ scale = global_ptr<float>(d.p3);
 
   if (!FULL) {
 #pragma unroll
@@ -140,7 +140,7 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   if (block_exists && (gc & 3) == 0 && r0 == 0) {
     scale[(size_t)by * nbc + bcol] = b.s32;
     // shared exponent of the block: biased exponent of X; X = 1 for an all-zero block
-    if (MX) ((uint8_t*)d.p4)[(size_t)by * nbc + bcol] = a16 ? (uint8_t)(__float_as_uint(b.x_scale) >> 23) : (uint8_t)127;
+    if (MX) global_ptr<uint8_t>(d.p4)[(size_t)by * nbc + bcol] = a16 ? (uint8_t)(__float_as_uint(b.x_scale) >> 23) : (uint8_t)127;
   }
   // hardware FP8 converters only if neither block of this wavefront can overflow
   const bool hw = (FMT == 1) && (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0);
@@ -156,13 +156,13 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
         if constexpr (MX) {
           const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, use_hw);
-          store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
+          store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
         } else {
           const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
-          uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+          GWS_GLOBAL uint16_t* dst = w_hat + (size_t)row * d.ld + col;
           if (FULL || t.nv[i] == 8) {
             if (STREAM) store16(dst, o);
-            else *(u32x4*)dst = o;
+            else *(GWS_GLOBAL u32x4*)dst = o;
           } else {
             store_partial(dst, o, t.nv[i]);
           }
@@ -204,7 +204,7 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
       for (int i = 0; i < 4; ++i) {
         if (!FULL && t.nv[i] == 0) continue;
         const uint32_t row = row_base + r0 + 8 * i;
-        store_codes<FMT>((uint8_t*)d.p1 + (size_t)row * d.ldc, col, gc4[i], FULL ? 8 : t.nv[i]);
+        store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, gc4[i], FULL ? 8 : t.nv[i]);
       }
     } else {
       const bf16x32 q = __builtin_amdgcn_cvt_scalef32_pk32_bf16_bf6(c, b.x_scale);
@@ -215,10 +215,10 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         if (!FULL && t.nv[i] == 0) continue;
         const uint32_t row = row_base + r0 + 8 * i;
         const u32x4 og = {o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
-        uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+        GWS_GLOBAL uint16_t* dst = w_hat + (size_t)row * d.ld + col;
         if (FULL || t.nv[i] == 8) {
           if (STREAM) store16(dst, og);
-          else *(u32x4*)dst = og;
+          else *(GWS_GLOBAL u32x4*)dst = og;
         } else {
           store_partial(dst, og, t.nv[i]);
         }
