@@ -7,11 +7,11 @@
 // therefore covers 8 rows x 128 contiguous bytes, the four waves of a workgroup
 // sit side by side (512 contiguous bytes per row), and the per-block reductions
 // (absmax, sum of g.*R) stay inside one wavefront: no LDS, no barrier.
-// A workgroup walks down `tiles_per_wg` consecutive block rows of its 256-column
-// strip (1 in the forward pass, up to 8 in the lighter backward pass, where the
-// per-workgroup set-up would otherwise show).  Latency is hidden by occupancy:
-// measured on MI355X, keeping the next tile's loads in flight inside a wavefront
-// costs more in registers than it gains.
+// A workgroup covers one such 32 x 256 tile in the forward pass and up to four
+// neighbouring column tiles in the lighter backward pass, where the per-wavefront
+// set-up would otherwise show.  Latency is hidden by occupancy: measured on
+// MI355X, keeping the next tile's loads in flight inside a wavefront costs more
+// in registers than it gains.
 // One Philox4x32-10 call yields the 16 bits x 8 elements of one 16-byte group,
 // so the noise lives only in registers (2 bytes per parameter of HBM traffic per
 // operand, Sec. 3.5; the 0.5 byte per parameter temporary of the paper is gone).
