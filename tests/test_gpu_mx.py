@@ -147,3 +147,12 @@ def test_argument_errors():
         gws.gws_sample_fwd_mx([d], [gws.MxOut(codes.view(-1)[1:4033].view(63, 64), xs, ldc=64)], gws.FMT_FP8_E4M3, 0)
     assert e.value.status == 3
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("fmt", MX_FMTS)
+def test_random_mix_of_many_small_and_ragged_tensors(fmt):
+    rng = np.random.default_rng(40 + fmt)
+    shapes = [(int(rng.integers(1, 150)), int(rng.integers(1, 1100))) for _ in range(64)]
+    shapes[3] = (0, 17)
+    shapes[9] = (32, 256)
+    check_mx(make_items(shapes, 2000 + 100 * fmt, user_seed=fmt), fmt, 6, pad=1)

@@ -252,3 +252,22 @@ def test_block_absmax_is_exact():
         ref = np.array([[wv[bi * 32:bi * 32 + 32, bj * 32:bj * 32 + 32].max() for bj in range(nbc)] for bi in range(nbr)],
                        dtype=np.float32)
         assert np.array_equal(out.cpu().numpy(), ref), (r, c)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_mixes_of_many_small_and_ragged_tensors(seed):
+    # more tensors than one launch holds, shapes from one element to several workgroup tiles wide:
+    # exercises the workgroup -> tensor lookup, the grouping of column tiles and every edge case of the tile code
+    rng = np.random.default_rng(seed)
+    n = 70
+    shapes = [(int(rng.integers(1, 200)), int(rng.integers(1, 1400))) for _ in range(n)]
+    shapes[5] = (0, 40)
+    shapes[17] = (64, 0)
+    shapes[23] = (32, 256)
+    shapes[40] = (33, 1025)
+    items = make_items(shapes, 1000 + 100 * seed, user_seed=seed)
+    fmt = FMTS[seed % 3]
+    outs = check_forward(items, fmt, step=seed)
+    for it, (_, scale) in zip(items, outs):
+        it["scale"] = scale
+    check_backward(items, step=seed, dw_mode="copy" if seed % 2 else "alias")
