@@ -17,9 +17,11 @@
  * Sec. 3.6 "Managing seed"): R is a pure function of (seed, step, row, column),
  * so a backward call with the seed and step of the forward call regenerates the
  * same R and no noise tensor is ever stored.  The 16 random bits of element
- * (i, j) are nibble (j & 7) of each of the four words of
+ * (i, j) are one nibble of each of the four words of
  *   Philox4x32-10(counter = (col0/8 + j>>3, row0 + i, step_lo, step_hi),
- *                 key     = (seed_lo, seed_hi)).
+ *                 key     = (seed_lo, seed_hi)),
+ * namely nibble (k >> 1) + 4 * (k & 1) with k = j & 7: even elements of a group of
+ * eight read the low 16-bit half of each word, odd elements the high half.
  */
 #ifndef GWS_H
 #define GWS_H
