@@ -127,10 +127,12 @@ def main():
                 e[2].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        fwd_ms = sum(ev[s][0].elapsed_time(ev[s][1]) for s in sampled) / len(sampled)
-        bwd_ms = sum(ev[s][1].elapsed_time(ev[s][2]) for s in sampled) / len(sampled)
+        fwd_all = sorted(ev[s][0].elapsed_time(ev[s][1]) for s in sampled)
+        bwd_all = sorted(ev[s][1].elapsed_time(ev[s][2]) for s in sampled)
+        fwd_ms, bwd_ms = sum(fwd_all) / len(fwd_all), sum(bwd_all) / len(bwd_all)
         return dict(params=params, blocks=blocks, n_launch=n_launch, wall_s=t1 - t0, fwd_ms=fwd_ms, bwd_ms=bwd_ms,
-                    sets=sets)
+                    fwd_ms_median=fwd_all[len(fwd_all) // 2], fwd_ms_min=fwd_all[0],
+                    bwd_ms_median=bwd_all[len(bwd_all) // 2], bwd_ms_min=bwd_all[0], sets=sets)
 
     if args.only_linear:
         print(json.dumps({"fused_linear": linear_bench(torch, gws, synth, dev)}))
@@ -202,9 +204,12 @@ def main():
                      "launch_ms": fwd_launch_ms, "bytes_per_launch": fwd_bytes / res["n_launch"],
                      "timing": f"HIP events around the call on every {EVENT_EVERY}th step of the timed region, minus "
                                "the reading of an empty event pair (empty_event_pair_ms), per launch",
-                     "call_ms_between_events": res["fwd_ms"], "empty_event_pair_ms": pair_ms,
+                     "call_ms_between_events": res["fwd_ms"], "call_ms_between_events_median": res["fwd_ms_median"],
+                     "call_ms_between_events_min": res["fwd_ms_min"], "empty_event_pair_ms": pair_ms,
                      "bwd": {"kernel": "sample_bwd_kernel", "launch_ms": bwd_launch_ms,
-                             "call_ms_between_events": res["bwd_ms"], "achieved": bwd_achieved,
+                             "call_ms_between_events": res["bwd_ms"],
+                             "call_ms_between_events_median": res["bwd_ms_median"],
+                             "call_ms_between_events_min": res["bwd_ms_min"], "achieved": bwd_achieved,
                              "frac": bwd_achieved / HBM_PEAK_GBS}},
         "paper_context": "paper reports 1.40% end-to-end tokens/s overhead (Llama2-134M, A100-40G, Table 1); "
                          "no params/s or GB/s figure exists for this path",
