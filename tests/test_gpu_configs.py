@@ -102,3 +102,65 @@ def test_config4_precision_sweep(fmt_name):
             assert d.scale[bi, bj].item() == ref_s[0, 0]
         del descs, pk
         torch.cuda.empty_cache()
+
+
+def test_one_tensor_beyond_4_gib_matches_its_shards_and_the_oracle():
+    # a ragged tensor of 2.29e9 elements (4.6 GB per buffer): byte offsets pass 2^32 inside one tensor.
+    # (a) every element equals what four row shards of about 1.15 GB each give through their origins,
+    # (b) sampled blocks, the last (ragged) block row and column among them, equal the oracle's.
+    rows, cols, ld = 40_011, 57_350, 57_352
+    assert rows * ld * 2 > 2 ** 32
+    step, fmt = 11, gws.FMT_FP8_E4M3
+    t = synth.make_tensor(90, rows, cols, device=DEV, ld=ld)
+    seed = gws.gws_derive_seed(3, 90)
+    nbr, nbc = synth.n_blocks(rows, cols)
+    w, g, bt = t["w"], t["g"], t["bt"]
+
+    def run(r0, r1, w_hat, scale, dw, dbt):
+        b0, b1 = r0 // 32, (r1 + 31) // 32
+        d = gws.TensorDesc(rows=r1 - r0, cols=cols, ld=ld, seed=seed, row0=r0, w=w[r0:r1], w_hat=w_hat[r0:r1],
+                           bt=bt[b0:b1], scale=scale[b0:b1], g=g[r0:r1], dw=dw[r0:r1], dbt=dbt[b0:b1])
+        gws.gws_sample_fwd([d], fmt, step)
+        gws.gws_sample_bwd([d], step)
+
+    def outputs():
+        return (w.clone(), torch.zeros(nbr, nbc, device=DEV), torch.zeros_like(g), torch.zeros(nbr, nbc, device=DEV))
+
+    whole = outputs()
+    run(0, rows, *whole)
+    torch.cuda.synchronize()
+    parts = outputs()
+    cuts = [0, 10_016, 20_000, 30_016, rows]
+    for r0, r1 in zip(cuts[:-1], cuts[1:]):
+        run(r0, r1, *parts)
+    torch.cuda.synchronize()
+    names = ("w_hat", "scale", "dw", "db_t")
+    for name, a, b in zip(names, whole, parts):
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a.view(torch.int32),
+                           b.view(torch.int16) if b.dtype == torch.bfloat16 else b.view(torch.int32)), name
+    del parts
+    w_hat, scale, dw, dbt = whole
+    assert torch.equal(w_hat[:, cols:].view(torch.int16), w[:, cols:].view(torch.int16)), "padding written"
+    assert torch.equal(dw[:, :cols].view(torch.int16), g[:, :cols].view(torch.int16))
+    assert not torch.equal(w_hat[-64:, :cols].view(torch.int16), w[-64:, :cols].view(torch.int16))
+
+    rng = np.random.default_rng(90)
+    picks = [(nbr - 1, nbc - 1), (nbr - 1, 0), (0, nbc - 1), (nbr - 2, nbc - 2), (0, 0)]
+    picks += [(int(rng.integers(0, nbr)), int(rng.integers(0, nbc))) for _ in range(30)]
+    first_beyond = 2 ** 32 // (2 * ld * 32) + 1                            # block rows whose bytes lie past 2^32
+    picks += [(int(rng.integers(first_beyond, nbr)), int(rng.integers(0, nbc))) for _ in range(29)]
+    beyond = 0
+    for bi, bj in picks:
+        r0, c0 = bi * 32, bj * 32
+        nr, nc = min(32, rows - r0), min(32, cols - c0)
+        beyond += (r0 * ld + c0) * 2 >= 2 ** 32
+        wb = synth.bits(w[r0:r0 + nr, c0:c0 + 32].contiguous())            # 32 wide: ld stays a multiple of 8
+        btb = bt[bi:bi + 1, bj:bj + 1].cpu().numpy()
+        ref_q, ref_s = oracle.sample_fwd(wb, btb, fmt, seed, step, cols=nc, row0=r0, col0=c0)
+        got = synth.bits(w_hat[r0:r0 + nr, c0:c0 + 32].contiguous())
+        assert (got[:, :nc] == ref_q[:, :nc]).all(), (bi, bj)
+        assert scale[bi, bj].item() == ref_s[0, 0], (bi, bj)
+        gb = synth.bits(g[r0:r0 + nr, c0:c0 + 32].contiguous())
+        _, ref_dbt, asum = oracle.sample_bwd(gb, ref_s, seed, step, cols=nc, row0=r0, col0=c0)
+        assert_dbt_close(dbt[bi:bi + 1, bj:bj + 1].cpu().numpy(), ref_dbt, asum, (bi, bj))
+    assert beyond >= 29
