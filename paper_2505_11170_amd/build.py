@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 SOURCES = ["gws_api.hip", "gws_sample.hip", "gws_linear.hip", "gws_gemm256.hip", "gws_gemm256_tn.hip"]
-HEADERS = ["gws_device.h", "gws_launch.h", "gws_sample_tile.h", "gws_mfma.h"]
+HEADERS = ["gws_device.h", "gws_launch.h", "gws_sample_tile.h", "gws_gemm256_core.h"]
 OUT = os.path.join(_HERE, "libgws.so")
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",

@@ -1,149 +1,32 @@
 // Large-tile BF16 MFMA GEMM for gfx950: Y[M x N] = X[M x K] * W, W stored [K x N] or
-// [N x K].  Used when M, N are multiples of 256 and K of 64.
-//
-// Workgroup = 256 threads = 2x2 wavefronts on a 256 x 256 x 64 block tile; a
-// wavefront owns 128 x 128 of the output as 4x4 v_mfma_f32_32x32x16_bf16 tiles
-// (256 accumulator registers per lane, one wavefront per SIMD).  LDS holds two
-// stages of both operand tiles (about 140 KB of the 160 KB): global loads for
-// step k+1 are issued before the MFMAs of step k and written to the other stage
-// afterwards, so there is one barrier per K-step.
-//   X tile and [N x K] weight tile: K-contiguous rows (144-byte pitch), one
-//     16-byte LDS read per MFMA operand.
-//   [K x N] weight tile: kept as stored (N-contiguous rows, 544-byte pitch) and
-//     read with the transposing LDS load (ds_read_b64_tr_b16): within a group of
-//     16 lanes, lanes 4j..4j+3 point at 16 consecutive n of row k0+j and lane i
-//     receives the four k of column n0+i.
+// [N x K].  Used when M, N are multiples of 256 and K of 64.  The tile itself (direct
+// global -> LDS loads, swizzled stages, pinned MFMA / LDS-read / load interleave) is in
+// gws_gemm256_core.h; here are the tile numbering, the plain kernel and the fused
+// sample-once kernel.
 // Tiles are numbered so that the 32 workgroups running together on one XCD
 // (workgroups are dealt round-robin to the 8 XCDs, each with its own L2) form an
 // 8 x 4 patch that shares 8 X panels and 4 W panels.
-// The epilogue stages the BF16 result in LDS and writes 16 bytes per lane.
 #include <atomic>
 
+#include "gws_gemm256_core.h"
 #include "gws_launch.h"
-#include "gws_mfma.h"
 #include "gws_sample_tile.h"
 
 namespace gws {
 
-// One 256 x 256 output tile.  `L` is the launch-order tile number (remapped below),
-// `wsrc` the weight operand (W, or the sampled w_hat).
+// One 256 x 256 output tile.  `L` is the launch-order tile number, `wsrc` the weight
+// operand (W, or the sampled w_hat).
 template <bool W_NK>
-__device__ __forceinline__ void gemm256_tile(const GemmArgs& g, const uint16_t* __restrict__ wsrc, uint32_t L,
-                                             uint16_t* lds) {
-  using namespace g256;
-  uint16_t* const As = lds;                                   // [2][TM][PA]
-  uint16_t* const Bs = lds + 2 * A_STAGE;                     // [2][...]
-  constexpr int B_STAGE = W_NK ? B_STAGE_NK : B_STAGE_KN;
-
-  const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const uint32_t wm = wave >> 1, wn = wave & 1;
-
+__device__ __forceinline__ void gemm256_tile(const GemmArgs& g, const uint16_t* __restrict__ wsrc, uint32_t L) {
   uint32_t tile_m, tile_n;
-  tile_of(L, g.M / TM, g.N / TN, tile_m, tile_n);
-  const uint32_t m0 = tile_m * TM, n0 = tile_n * TN;
-
-  // ---- global -> register staging: 8 + 8 sixteen-byte chunks per thread ----
-  const uint16_t* a_src = g.x + (size_t)(m0 + (tid >> 3)) * g.ldx + (tid & 7) * 8;   // + 32 rows per i
-  const uint16_t* b_src;
-  if (W_NK) b_src = wsrc + (size_t)(n0 + (tid >> 3)) * g.ldw + (tid & 7) * 8;          // + 32 rows per i
-  else b_src = wsrc + (size_t)(tid >> 5) * g.ldw + n0 + (tid & 31) * 8;                // + 8 k-rows per i
-  u32x4 ra[8], rb[8];
-  auto load_global = [&](uint32_t kt) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      ra[i] = *(const u32x4*)(a_src + (size_t)(32 * i) * g.ldx + kt * TK);
-      if (W_NK) rb[i] = *(const u32x4*)(b_src + (size_t)(32 * i) * g.ldw + kt * TK);
-      else rb[i] = *(const u32x4*)(b_src + (size_t)(kt * TK + 8 * i) * g.ldw);
-    }
-  };
-  auto store_lds = [&](uint32_t stage) {
-    uint16_t* a_dst = As + stage * A_STAGE + (tid >> 3) * PA + (tid & 7) * 8;
-    uint16_t* b_dst = W_NK ? Bs + stage * B_STAGE + (tid >> 3) * PA + (tid & 7) * 8
-                           : Bs + stage * B_STAGE + (tid >> 5) * PB_KN + (tid & 31) * 8;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *(u32x4*)(a_dst + 32 * i * PA) = ra[i];
-      if (W_NK) *(u32x4*)(b_dst + 32 * i * PA) = rb[i];
-      else *(u32x4*)(b_dst + 8 * i * PB_KN) = rb[i];
-    }
-  };
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  // per-lane LDS read offsets (elements)
-  const uint32_t a_rd = (128 * wm + (lane & 31)) * PA + (lane >> 5) * 8;          // + 32 i rows, + 16 ks
-  const uint32_t b_rd_nk = (128 * wn + (lane & 31)) * PA + (lane >> 5) * 8;
-  // transposing read: group = lane / 16 -> n half (group & 1), k half (group >> 1);
-  // lane i of a group points at row k0 + i/4, columns n0 + 4 (i%4)
-  const uint32_t li = lane & 15, grp = lane >> 4;
-  const uint32_t b_rd_kn = ((grp >> 1) * 8 + (li >> 2)) * PB_KN + 128 * wn + (grp & 1) * 16 + (li & 3) * 4;
-
-  const uint32_t nk = g.K / TK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    const uint32_t st = kt & 1;
-    if (kt + 1 < nk) load_global(kt + 1);
-    const uint16_t* a_s = As + st * A_STAGE;
-    const uint16_t* b_s = Bs + st * B_STAGE;
-#pragma unroll 2
-    for (int ks = 0; ks < TK / 16; ++ks) {
-      Frag8 fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i].u = *(const u32x4*)(a_s + a_rd + 32 * i * PA + ks * 16);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (W_NK) {
-          fb[j].u = *(const u32x4*)(b_s + b_rd_nk + 32 * j * PA + ks * 16);
-        } else {
-          const uint16_t* p = b_s + b_rd_kn + (ks * 16) * PB_KN + 32 * j;
-          fb[j].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p);
-          fb[j].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p + 4 * PB_KN));
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_lds(st ^ 1);
-    __syncthreads();
-  }
-
-  // ---- epilogue: fp32 -> BF16 (RNE) into LDS, then 16-byte rows to global ----
-  // acc[i][j][e]: row 32 i + 8 (e/4) + 4 (lane/32) + e%4, column 32 j + lane%32 of the wave tile
-  uint16_t* cs = lds + wave * (128 * PC);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const uint32_t row = 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        cs[row * PC + 32 * j + (lane & 31)] = (uint16_t)bf16_rne_bits(acc[i][j][e]);
-      }
-  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS writes have landed
-  __builtin_amdgcn_wave_barrier();
-  uint16_t* y = g.y + (size_t)(m0 + 128 * wm) * g.ldy + n0 + 128 * wn;
-#pragma unroll 4
-  for (int it = 0; it < 32; ++it) {
-    const uint32_t row = it * 4 + (lane >> 4), c = (lane & 15) * 8;
-    *(u32x4*)(y + (size_t)row * g.ldy + c) = *(const u32x4*)(cs + row * PC + c);
-  }
+  tile_of(L, g.M / g256::TM, g.N / g256::TN, tile_m, tile_n);
+  gemm256_core<false, !W_NK>(g.x, g.ldx, wsrc, g.ldw, g.y, g.ldy, g.K / g256::TK, tile_m * g256::TM,
+                             tile_n * g256::TN, NoHook{});
 }
 
 template <bool W_NK>
 __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  gemm256_tile<W_NK>(g, g.w, blockIdx.x, lds);
+  gemm256_tile<W_NK>(g, g.w, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -240,7 +123,6 @@ __device__ __forceinline__ void sample_tiles(const GemmArgs& g, const TileDesc& 
 
 template <int FMT, bool W_NK>
 __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs g, const uint32_t epoch) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   __shared__ uint32_t gave_up;
   const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   TileDesc d;  // the stored weight as the forward pass describes it (cols is a multiple of 64 here)
@@ -264,8 +146,8 @@ __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs 
   // ---- phase 2: GEMM tiles on w_hat ----
   const uint32_t total = (g.M / g256::TM) * (g.N / g256::TN);
   for (uint32_t L = blockIdx.x; L < total; L += gridDim.x) {
-    gemm256_tile<W_NK>(g, g.w_hat, L, lds);
-    __syncthreads();  // the epilogue staging is read before the next tile overwrites it
+    gemm256_tile<W_NK>(g, g.w_hat, L);
+    __syncthreads();  // the epilogue staging is read before the next tile's loads overwrite it
   }
 }
 
@@ -273,41 +155,18 @@ bool gemm256_applicable(const GemmArgs& g) {
   return g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 && g.M > 0 && g.N > 0 && g.K > 0;
 }
 
-// The kernels need more dynamic LDS than the default limit; the attribute is raised once per
-// kernel and process (not per launch: nothing but the launch itself is issued on a stream that
-// may be under capture).
-template <class K>
-static bool raise_lds_limit(K kernel, size_t lds) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
-}
-
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream) {
   const uint64_t tiles = (uint64_t)(g.M / g256::TM) * (g.N / g256::TN);
   if (tiles >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
-  const size_t lds = g256::lds_bytes(w_is_nk != 0);
-  if (w_is_nk) {
-    static const bool ok = raise_lds_limit(gemm256_kernel<true>, g256::lds_bytes(true));
-    if (!ok) return GWS_ERR_LAUNCH;
-    hipLaunchKernelGGL(gemm256_kernel<true>, dim3((uint32_t)tiles), dim3(256), lds, stream, g);
-  } else {
-    static const bool ok = raise_lds_limit(gemm256_kernel<false>, g256::lds_bytes(false));
-    if (!ok) return GWS_ERR_LAUNCH;
-    hipLaunchKernelGGL(gemm256_kernel<false>, dim3((uint32_t)tiles), dim3(256), lds, stream, g);
-  }
+  if (w_is_nk) hipLaunchKernelGGL(gemm256_kernel<true>, dim3((uint32_t)tiles), dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL(gemm256_kernel<false>, dim3((uint32_t)tiles), dim3(256), 0, stream, g);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
 template <int FMT>
-static int launch_fused_fmt(const GemmArgs& g, int w_is_nk, uint32_t grid, size_t lds, uint32_t epoch, hipStream_t s) {
-  if (w_is_nk) {
-    static const bool ok = raise_lds_limit(linear256_fused_kernel<FMT, true>, g256::lds_bytes(true));
-    if (!ok) return GWS_ERR_LAUNCH;
-    hipLaunchKernelGGL((linear256_fused_kernel<FMT, true>), dim3(grid), dim3(256), lds, s, g, epoch);
-  } else {
-    static const bool ok = raise_lds_limit(linear256_fused_kernel<FMT, false>, g256::lds_bytes(false));
-    if (!ok) return GWS_ERR_LAUNCH;
-    hipLaunchKernelGGL((linear256_fused_kernel<FMT, false>), dim3(grid), dim3(256), lds, s, g, epoch);
-  }
+static int launch_fused_fmt(const GemmArgs& g, int w_is_nk, uint32_t grid, uint32_t epoch, hipStream_t s) {
+  if (w_is_nk) hipLaunchKernelGGL((linear256_fused_kernel<FMT, true>), dim3(grid), dim3(256), 0, s, g, epoch);
+  else hipLaunchKernelGGL((linear256_fused_kernel<FMT, false>), dim3(grid), dim3(256), 0, s, g, epoch);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
@@ -327,11 +186,10 @@ int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t 
   static std::atomic<uint32_t> next_epoch{1};
   uint32_t epoch = next_epoch.fetch_add(1);
   if (epoch == 0) epoch = next_epoch.fetch_add(1);
-  const size_t lds = g256::lds_bytes(w_is_nk != 0);
   switch (fmt) {
-    case GWS_FMT_BF16: return launch_fused_fmt<0>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
-    case GWS_FMT_FP8_E4M3: return launch_fused_fmt<1>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
-    case GWS_FMT_FP6_E3M2: return launch_fused_fmt<2>(g, w_is_nk, (uint32_t)cus, lds, epoch, stream);
+    case GWS_FMT_BF16: return launch_fused_fmt<0>(g, w_is_nk, (uint32_t)cus, epoch, stream);
+    case GWS_FMT_FP8_E4M3: return launch_fused_fmt<1>(g, w_is_nk, (uint32_t)cus, epoch, stream);
+    case GWS_FMT_FP6_E3M2: return launch_fused_fmt<2>(g, w_is_nk, (uint32_t)cus, epoch, stream);
     default: return GWS_ERR_FORMAT;
   }
 }

@@ -1,0 +1,264 @@
+// One 256 x 256 output tile of a BF16 GEMM on gfx950, shared by the large-tile kernels
+// (internal to csrc/).
+//
+// Workgroup = 256 threads = 2x2 wavefronts, K-steps of 64; a wavefront owns 128 x 128 of the
+// output as 4x4 v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers per lane, one
+// wavefront per SIMD).
+//
+// Operand tiles travel global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
+// staging registers), into two stages per operand.  Such a load writes its 64 lanes to 1 KiB of
+// consecutive LDS, so the layout is unpadded and bank conflicts are avoided by choosing which
+// 16-byte chunk of the tile each lane fetches (an XOR swizzle of the chunk index):
+//   operand stored contraction-contiguous (X; a weight stored [N x K]): tile = 256 rows of
+//     128 bytes; chunk c of row r sits in slot c ^ (r % 8); one ds_read_b128 per MFMA operand;
+//   operand stored output-contiguous (a weight stored [K x N]; both operands of the
+//     weight-gradient GEMM): tile = 64 k-rows of 512 bytes; chunk c of row k sits in slot
+//     c ^ 4 (k % 4); read with the transposing LDS load (ds_read_b64_tr_b16: within 16 lanes,
+//     lanes 4j..4j+3 point at 16 consecutive outputs of row k0+j and lane i receives the four k
+//     of output o0+i), two per MFMA operand.
+// The four stage arrays are separate LDS variables: that is how the compiler can tell that a
+// load into one stage does not feed the reads of the other, and does not wait for it.
+//
+// With one wavefront per SIMD nothing else hides latency, and left to itself the scheduler
+// puts each LDS read right before its use and the 16 loads of a K-step in one burst, both of
+// which stall the MFMA pipe.  The order of the main loop is therefore written out and pinned
+// (a scheduling barrier after every step): each MFMA is followed by at most one LDS read (for
+// the next 16-deep slice, into the other fragment buffer) and, in the last slice of a K-step,
+// one load.  The single barrier of a K-step sits before that last slice: by then every
+// wavefront has issued (and the barrier waits for) its reads of the stage, so the stage can be
+// refilled for the step after next, and the other stage, whose loads were issued a whole K-step
+// earlier, is complete and its first fragments can be fetched under the last 16 MFMAs.
+#pragma once
+
+#include "gws_device.h"
+#include "gws_launch.h"
+
+namespace gws {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define GWS_LDS __attribute__((address_space(3)))
+
+namespace g256 {
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int STAGE = 256 * 64;   // elements of one operand tile (32 KiB), either layout
+constexpr int PC = 128 + 8;       // epilogue pitch of a wavefront's staging rows (elements)
+static_assert(64 * PC <= STAGE, "half a wavefront tile is staged in one stage array");
+}  // namespace g256
+
+union Frag8 {
+  u32x4 u;
+  bf16x8 v;
+  i16x4 h[2];
+};
+
+// XCD-aware tile numbering: launch-order number L -> (tile_m, tile_n) of an mt x nt grid of
+// tiles.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; XCD x gets
+// a contiguous range of an order that walks 8 m-tiles down before moving one n-tile right,
+// so the 32 workgroups running together on an XCD form an 8 x 4 patch sharing 8 + 4 panels.
+__device__ __forceinline__ void tile_of(uint32_t L, uint32_t mt, uint32_t nt, uint32_t& tile_m, uint32_t& tile_n) {
+  const uint32_t total = mt * nt;
+  const uint32_t per = total / 8, rem = total % 8, x = L % 8, j = L / 8;
+  L = x * per + (x < rem ? x : rem) + j;            // XCD x owns `per` tiles (+1 for the first `rem`)
+  const uint32_t band_sz = 8 * nt;                   // tiles in a band of 8 m-tiles
+  const uint32_t band = L / band_sz, r = L % band_sz;
+  const uint32_t mrows = (band * 8 + 8 <= mt) ? 8 : (mt - band * 8);  // last band may be short
+  tile_n = r / mrows;
+  tile_m = band * 8 + r % mrows;
+}
+
+// C tile at (m0, n0) = sum over nk K-steps of A-tile * B-tile, written as BF16 (one RNE) to
+// y[(m0 + r) * ldy + n0 + c].
+//   A_OC = false: a[(m0 + r) * lda + k]   (contraction-contiguous)   true: a[k * lda + m0 + r]
+//   B_OC = false: b[(n0 + c) * ldb + k]                               true: b[k * ldb + n0 + c]
+// hook(it, row, col, v) is called for every 16-byte group of the BF16 result on its way out:
+// a wavefront writes its 128 x 128 part in 32 steps `it` of 4 rows, lane = (row % 4, col / 8).
+// Requires nk >= 1 and all 256 threads; ends with every wavefront past its last LDS access
+// except its own epilogue staging (callers that loop over tiles put a barrier between tiles).
+template <bool A_OC, bool B_OC, class Hook>
+__device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uint32_t lda,
+                                             const uint16_t* __restrict__ b, uint32_t ldb, uint16_t* __restrict__ y,
+                                             uint32_t ldy, uint32_t nk, uint32_t m0, uint32_t n0, Hook&& hook) {
+  using namespace g256;
+  __shared__ __attribute__((aligned(16))) uint16_t A0[STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t A1[STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t B0[STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t B1[STAGE];
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = wave >> 1, wn = wave & 1;
+
+  // ---- loads: wave-uniform base + per-lane byte offset; instruction q (0..7) of a wavefront fills
+  // 1 KiB at (wave * 8 + q) * 1 KiB of the stage ----
+  struct Src {
+    const GWS_GLOBAL char* base;
+    uint32_t voff[2];   // per-lane byte offset (output-contiguous: depends on q % 2)
+    uint32_t ld;
+  };
+  auto make_src = [&](bool oc, const uint16_t* p, uint32_t ld, uint32_t o0) {
+    Src s;
+    s.ld = ld;
+    if (!oc) {  // rows 64 wave + 8 q + lane/8; slot lane%8 holds chunk slot ^ (row % 8)
+      s.base = (const GWS_GLOBAL char*)(p + (size_t)(o0 + 64 * wave) * ld);
+      s.voff[0] = s.voff[1] = ((lane >> 3) * ld + (((lane & 7) ^ (lane >> 3)) * 8)) * 2;
+    } else {    // k-rows 16 wave + 2 q + lane/32; slot lane%32 holds chunk slot ^ 4 (k % 4), k % 4 = 2 (q%2) + lane/32
+      const uint32_t kb = lane >> 5;
+      s.base = (const GWS_GLOBAL char*)(p + (size_t)(16 * wave) * ld + o0);
+      s.voff[0] = (kb * ld + (((lane & 31) ^ ((0 + kb) << 2)) * 8)) * 2;
+      s.voff[1] = (kb * ld + (((lane & 31) ^ ((2 + kb) << 2)) * 8)) * 2;
+    }
+    return s;
+  };
+  const Src sa = make_src(A_OC, a, lda, m0), sb = make_src(B_OC, b, ldb, n0);
+  auto load1 = [&](bool oc, const Src& s, uint16_t* stage, uint32_t kt, int q) {
+    const size_t uni = oc ? (size_t)(kt * TK + 2 * q) * s.ld : (size_t)(8 * q) * s.ld + kt * TK;   // elements
+    __builtin_amdgcn_global_load_lds((const GWS_GLOBAL void*)(s.base + uni * 2 + s.voff[q & 1]),
+                                     (GWS_LDS void*)(stage + (wave * 8 + q) * 512), 16, 0, 0);
+  };
+  // load n (0..15) of a K-step: even n -> A, odd n -> B
+  auto load_n = [&](uint16_t* As, uint16_t* Bs, uint32_t kt, int n) {
+    if (!(n & 1)) load1(A_OC, sa, As, kt, n >> 1);
+    else load1(B_OC, sb, Bs, kt, n >> 1);
+  };
+
+  // ---- fragment reads: per-lane element offsets into a stage ----
+  const uint32_t li = lane & 15, grp = lane >> 4, sw = (li >> 2) & 3;
+  uint32_t a_off[4], b_off[4];   // contraction-contiguous: per ks; output-contiguous: per fragment index
+  auto make_off = [&](bool oc, uint32_t w, uint32_t (&off)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (!oc) off[t] = (128 * w + (lane & 31)) * 64 + (((2 * t + (lane >> 5)) ^ (lane & 7)) * 8);
+      else off[t] = ((grp >> 1) * 8 + (li >> 2)) * 256 + (16 * w + 4 * (t ^ sw) + 2 * (grp & 1) + ((li >> 1) & 1)) * 8 + (li & 1) * 4;
+    }
+  };
+  make_off(A_OC, wm, a_off);
+  make_off(B_OC, wn, b_off);
+  // read `half` of fragment f (0..3) of slice ks from a stage
+  auto read_frag = [&](bool oc, const uint32_t (&off)[4], Frag8& fr, const uint16_t* stage, int ks, int f, int half) {
+    if (!oc) {
+      fr.u = *(const u32x4*)(stage + off[ks] + f * 32 * 64);
+    } else {
+      const uint16_t* p = stage + off[f] + ks * 16 * 256 + half * 4 * 256;
+      fr.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GWS_LDS i16x4*)p);
+    }
+  };
+  constexpr int RA = A_OC ? 2 : 1, RB = B_OC ? 2 : 1;   // LDS reads per fragment
+  constexpr int NR = 4 * RA + 4 * RB;                   // reads per slice (<= 16)
+  Frag8 fa[2][4], fb[2][4];
+  // read n (0..NR-1) of slice (stage, ks) into fragment buffer `buf`, in the order the MFMAs need them:
+  // A fragment 0, B fragments 0..3, A fragments 1..3
+  auto read_n = [&](int buf, const uint16_t* As, const uint16_t* Bs, int ks, int n) {
+    if (n < RA) {
+      read_frag(A_OC, a_off, fa[buf][0], As, ks, 0, n);
+    } else if (n < RA + 4 * RB) {
+      const int m = n - RA;
+      read_frag(B_OC, b_off, fb[buf][m / RB], Bs, ks, m / RB, m % RB);
+    } else {
+      const int m = n - RA - 4 * RB;
+      read_frag(A_OC, a_off, fa[buf][1 + m / RA], As, ks, 1 + m / RA, m % RA);
+    }
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  auto mfma_n = [&](int buf, int n) {
+    const int i = n >> 2, j = n & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i].v, fb[buf][j].v, acc[i][j], 0, 0, 0);
+  };
+
+  // One K-step on the stage (Ac, Bc).  On entry fragment buffer 0 holds (or is receiving) slice 0
+  // of this stage and the loads of the other stage (An, Bn) are in flight; on exit the same holds
+  // with the stages swapped, and K-step `kn` is on its way into (Ac, Bc).
+  auto kstep = [&](uint16_t* Ac, uint16_t* Bc, uint16_t* An, uint16_t* Bn, uint32_t kn) {
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+#pragma unroll
+      for (int n = 0; n < 16; ++n) {
+        mfma_n(ks & 1, n);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n < NR) {
+          read_n((ks + 1) & 1, Ac, Bc, ks + 1, n);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of the other stage has landed
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      mfma_n(1, n);
+      __builtin_amdgcn_sched_barrier(0);
+      load_n(Ac, Bc, kn, n);
+      __builtin_amdgcn_sched_barrier(0);
+      if (n < NR) {
+        read_n(0, An, Bn, 0, n);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
+  // Past the last K-step the loads refetch that step into the stage nobody reads any more and
+  // the fragment reads go unused: no branches in the loop body.
+  const uint32_t last = nk - 1;
+#pragma unroll
+  for (int n = 0; n < 16; ++n) load_n(A0, B0, 0, n);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < 16; ++n) load_n(A1, B1, last < 1 ? last : 1, n);
+#pragma unroll
+  for (int n = 0; n < NR; ++n) read_n(0, A0, B0, 0, n);
+  uint32_t kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    kstep(A0, B0, A1, B1, kt + 2 < last ? kt + 2 : last);
+    kstep(A1, B1, A0, B0, kt + 3 < last ? kt + 3 : last);
+  }
+  if (kt < nk) kstep(A0, B0, A1, B1, last);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // the refetches have landed before the epilogue reuses LDS
+  __syncthreads();
+
+  // ---- epilogue: fp32 -> BF16 (RNE) into this wavefront's own stage array, 64 rows at a time,
+  // then 16-byte groups to global ----
+  // acc[i][j][e]: row 32 i + 8 (e/4) + 4 (lane/32) + e%4, column 32 j + lane%32 of the wavefront tile
+  uint16_t* cs = wave == 0 ? A0 : wave == 1 ? A1 : wave == 2 ? B0 : B1;
+  uint16_t* yw = y + (size_t)(m0 + 128 * wm) * ldy + n0 + 128 * wn;
+  const uint32_t lr = lane >> 4, c = (lane & 15) * 8;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const uint32_t row = 32 * i2 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          cs[row * PC + 32 * j + (lane & 31)] = (uint16_t)bf16_rne_bits(acc[2 * h + i2][j][e]);
+        }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS writes have landed
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+      const uint32_t row = it * 4 + lr;
+      const u32x4 v = *(const u32x4*)(cs + row * PC + c);
+      *(u32x4*)(yw + (size_t)(64 * h + row) * ldy + c) = v;
+      hook(16 * h + it, 64 * h + row, c, v);
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // the reads are done before the second half overwrites them
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+struct NoHook {
+  __device__ __forceinline__ void operator()(int, uint32_t, uint32_t, const u32x4&) const {}
+};
+
+}  // namespace gws
