@@ -487,7 +487,8 @@ def linear_bench(torch, gws, synth, dev):
         "bwd_w_plain": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd_plain, 0),
         "bwd_w_unfused": bwd_unfused,
         "bwd_w_torch": lambda: torch.matmul(x.t(), dy, out=dw),
-        "fused": lambda: gws.gws_linear_fwd(x, d_full, y, fmt, 0),
+        "fused": lambda: gws.gws_linear_fwd_mode(x, d_full, y, fmt, 0, gws.LINEAR_SAMPLE_ONCE),
+        "auto": lambda: gws.gws_linear_fwd(x, d_full, y, fmt, 0),
         "unfused": unfused,
         "plain": lambda: gws.gws_gemm_bf16(x, w, y),
         "plain_what": lambda: gws.gws_gemm_bf16(x, w_hat, y),
@@ -509,10 +510,13 @@ def linear_bench(torch, gws, synth, dev):
     med = {k: sorted(v)[len(v) // 2] for k, v in bursts.items()}
     t_fused, t_unfused, t_plain, t_plain_what = med["fused"], med["unfused"], med["plain"], med["plain_what"]
     t_torch, t_torch_what, t_unfused_torch, t_sample = med["torch"], med["torch_what"], med["unfused_torch"], med["sample"]
-    t_inop = _time_ms(torch, lambda: gws.gws_linear_fwd(x, d_inop, y, fmt, 0), 10)
+    t_inop = _time_ms(torch, lambda: gws.gws_linear_fwd_mode(x, d_inop, y, fmt, 0, gws.LINEAR_IN_OPERAND), 10)
+    t_auto = med["auto"]
     flop = 2.0 * M * K * N
     best_plain = min(t_plain, t_torch)
     return {"shape": [M, K, N],
+            "linear_fwd_auto_ms": t_auto, "auto_overhead_pct_vs_own_plain": 100.0 * (t_auto - t_plain) / t_plain,
+            "auto_overhead_pct_vs_best_plain": 100.0 * (t_auto - best_plain) / best_plain,
             "fused_sample_once_ms": t_fused, "fused_in_operand_ms": t_inop, "unfused_own_gemm_ms": t_unfused,
             "unfused_torch_gemm_ms": t_unfused_torch, "sample_only_ms": t_sample,
             "plain_own_ms": t_plain, "plain_own_on_w_hat_ms": t_plain_what,

@@ -3,7 +3,7 @@
  *
  * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
  * every other pointer is host memory.  The library allocates no device memory,
- * keeps no global state (one exception is stated at gws_linear_fwd) and is
+ * keeps no global state (one exception is stated at gws_linear_fwd_mode) and is
  * thread-safe.  All GPU work is enqueued asynchronously on the given stream (a
  * hipStream_t passed as void*, NULL = the default stream); no call synchronises.
  * The return value is a gws_status and reports argument and launch errors only;
@@ -152,9 +152,9 @@ typedef struct gws_mx_out {
 int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, uint64_t step,
                       void* stream);
 
-/* Fused sampled-weight linear: Y = X * w_hat with w_hat produced as in
- * gws_sample_fwd inside the GEMM kernel (the paper, Sec. 3.5 "Separate kernels",
- * keeps sampling and matmul apart; this is the fused alternative).
+/* Sampled-weight linear: Y = X * w_hat with w_hat produced as in gws_sample_fwd (the
+ * paper, Sec. 3.5 "Separate kernels", keeps sampling and matmul apart; the fused kernels
+ * here are the alternative, and the call picks whichever is faster).
  *   x : device BF16 [M x K], leading dimension ldx
  *   w : one descriptor (host).  w->w is [K x N] (rows = K, cols = N) or, when
  *       w_is_nk != 0, [N x K] (rows = N, cols = K; Y = X * w_hat^T).
@@ -162,18 +162,31 @@ int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, 
  *   y : device BF16 [M x N], leading dimension ldy; fp32 accumulation, one
  *       round-to-nearest-even to BF16.
  * K and N must be multiples of 32; ldx, ldy multiples of 8.
- * Two kernels serve this call.  When w_hat/scale are requested and M, N are
- * multiples of 256 and K of 64, one persistent launch samples every block once
- * (all workgroups together), meets at a device-wide arrival barrier kept in a few
- * device words of the library, and runs the GEMM on w_hat; two such calls must
- * not run concurrently on one GPU, and on a stream that is being captured into a
- * graph the call records the sampling kernel followed by the plain GEMM on w_hat
- * instead (same bytes, no state).  Otherwise the sampling sits in the weight
- * operand load of every output tile (no w_hat round trip, each block resampled
- * per tile row).  Both give bit-identical w_hat and Y.                          */
+ * Three ways to the same bytes (w_hat, scale and Y are bit-identical between them):
+ *   GWS_LINEAR_IN_OPERAND   one kernel; the sampling sits in the weight operand load of every
+ *                           output tile (no w_hat round trip; each block is resampled once per
+ *                           128 rows of X).  Any shape; w_hat/scale optional.
+ *   GWS_LINEAR_SAMPLE_ONCE  one persistent kernel: all workgroups sample every block once,
+ *                           meet at a device-wide arrival barrier kept in a few device words of
+ *                           the library, and run the GEMM on w_hat.  Needs w_hat/scale, M and N
+ *                           multiples of 256 and K of 64 (GWS_ERR_SHAPE otherwise).  Two such
+ *                           calls must not run concurrently on one GPU; on a stream that is being
+ *                           captured into a graph the call records the two kernels below instead.
+ *   GWS_LINEAR_TWO_KERNELS  the sampling kernel of gws_sample_fwd, then the plain GEMM on w_hat.
+ *                           Needs w_hat/scale (GWS_ERR_NULL otherwise); no state.
+ *   GWS_LINEAR_AUTO         two kernels when w_hat/scale are given and M > 128, else in-operand:
+ *                           the faster choice as measured on MI355X.
+ * gws_linear_fwd is gws_linear_fwd_mode with GWS_LINEAR_AUTO.                              */
+#define GWS_LINEAR_AUTO 0
+#define GWS_LINEAR_SAMPLE_ONCE 1
+#define GWS_LINEAR_IN_OPERAND 2
+#define GWS_LINEAR_TWO_KERNELS 3
 int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
                    const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
                    void* y, int64_t ldy, void* stream);
+int gws_linear_fwd_mode(const void* x, int64_t M, int64_t K, int64_t ldx,
+                        const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
+                        void* y, int64_t ldy, int mode, void* stream);
 
 /* Weight gradient of the sampled-weight linear with the reduction of Eq. 4 in the GEMM's
  * epilogue (the linear's backward pass, paper Eq. 2, applied to w_hat):

@@ -89,7 +89,7 @@ constexpr int kAbsmaxOnly = -2;  // the backward launch shape, block-maximum ker
 // `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
 // `mx` (one per tensor, forward only) switches the output to MX element codes and block scales.
 int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx_out* mx, bool fwd, int fmt,
-                uint64_t step, hipStream_t stream) {
+                uint64_t step, hipStream_t stream, bool keep = false) {
   // Tiles per workgroup.  Forward: one (most workgroups, fewest registers; measured best).
   // Backward does less per tile, so the per-wavefront set-up shows: a workgroup takes up to
   // four neighbouring column tiles while at least ~3000 workgroups (12 per compute unit)
@@ -115,7 +115,7 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
     int rc = (!fwd && fmt == kAbsmaxOnly) ? launch_block_absmax(a, (uint32_t)wgs, stream)
              : !fwd ? launch_sample_bwd(a, (uint32_t)wgs, stream)
              : fmt == kCopyOnly ? launch_copy_tiles(a, (uint32_t)wgs, stream)
-                                : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, stream);
+                                : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, keep, stream);
     a.n = 0;
     wgs = 0;
     for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
@@ -273,10 +273,11 @@ int gws_noise_packed(void* out, int64_t rows, int64_t cols, int64_t row0, int64_
                              (uint32_t)(col0 / 8), seed, step, (hipStream_t)stream);
 }
 
-int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
-                   int fmt, uint64_t step, void* y, int64_t ldy, void* stream) {
+int gws_linear_fwd_mode(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
+                        int fmt, uint64_t step, void* y, int64_t ldy, int mode, void* stream) {
   if (!w) return GWS_ERR_NULL;
   if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  if (mode < GWS_LINEAR_AUTO || mode > GWS_LINEAR_TWO_KERNELS) return GWS_ERR_FORMAT;
   int rc = check_shape(*w);
   if (rc != GWS_OK) return rc;
   const int64_t Kw = w_is_nk ? w->cols : w->rows, N = w_is_nk ? w->rows : w->cols;
@@ -298,21 +299,34 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_t
   g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
   g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
   g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
-  // The sample-once kernel tells its calls apart by an epoch passed as a kernel argument; a
-  // captured launch would replay one epoch against the synchronisation words it left behind.
-  // Under stream capture the same bytes come from two stateless launches instead: the
-  // sampling kernel, then the plain GEMM on w_hat.
-  if (linear256_fused_applicable(g)) {
+  if (mode == GWS_LINEAR_AUTO) {
+    // Measured on MI355X: once more than one row of output tiles shares the weight, sampling it
+    // once with the streaming kernel and running the plain GEMM on w_hat beats both fused kernels.
+    mode = (w->w_hat && M > 128) ? GWS_LINEAR_TWO_KERNELS : GWS_LINEAR_IN_OPERAND;
+  }
+  if (mode == GWS_LINEAR_TWO_KERNELS && !w->w_hat) return GWS_ERR_NULL;
+  if (mode == GWS_LINEAR_SAMPLE_ONCE) {
+    if (!linear256_fused_applicable(g)) return GWS_ERR_SHAPE;
+    // The sample-once kernel tells its calls apart by an epoch passed as a kernel argument; a
+    // captured launch would replay one epoch against the synchronisation words it left behind.
+    // Under stream capture the same bytes come from the two stateless launches instead.
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     if (stream != nullptr && hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) return GWS_ERR_LAUNCH;
-    if (capture != hipStreamCaptureStatusNone) {
-      rc = run_batched(w, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream);
-      if (rc != GWS_OK) return rc;
-      g.w = g.w_hat;
-      return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
-    }
+    if (capture != hipStreamCaptureStatusNone) mode = GWS_LINEAR_TWO_KERNELS;
   }
-  return launch_gemm(g, w_is_nk, 1, fmt, (hipStream_t)stream);
+  if (mode == GWS_LINEAR_TWO_KERNELS) {
+    rc = run_batched(w, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, /*keep=*/true);
+    if (rc != GWS_OK) return rc;
+    g.w = g.w_hat;
+    return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+  }
+  return launch_gemm(g, w_is_nk, mode == GWS_LINEAR_SAMPLE_ONCE ? kFusedSampleOnce : kFusedInOperand, fmt,
+                     (hipStream_t)stream);
+}
+
+int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
+                   int fmt, uint64_t step, void* y, int64_t ldy, void* stream) {
+  return gws_linear_fwd_mode(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, GWS_LINEAR_AUTO, stream);
 }
 
 int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w,
@@ -388,6 +402,6 @@ const char* gws_status_string(int status) {
   }
 }
 
-int gws_version(void) { return 4; }
+int gws_version(void) { return 5; }
 
 }  // extern "C"

@@ -54,7 +54,7 @@ struct LaunchArgs {
 };
 static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the size verified on the device");
 
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, hipStream_t stream);
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream);
 int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_copy_tiles(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_block_absmax(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
@@ -75,6 +75,9 @@ struct GemmArgs {
   uint32_t row0, cg0, seed_lo, seed_hi, step_lo, step_hi;
   float* dbt;          // weight-gradient GEMM only: dL/db_t per block (with scale as input)
 };
+// fused: 0 = plain GEMM on g.w; kFusedSampleOnce = cooperative sampling prologue + GEMM on w_hat (needs
+// linear256_fused_applicable); kFusedInOperand = sampling in the weight operand load of every tile
+constexpr int kFusedSampleOnce = 1, kFusedInOperand = 2;
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);

@@ -105,14 +105,16 @@ __device__ __forceinline__ void walk_tiles(const LaunchArgs& a, const TileDesc& 
 }
 
 // MX: write element codes and E8M0 block scales instead of the BF16 container.
-template <int FMT, bool MX = false>
+// STREAM: non-temporal stores of w_hat (right when it is not read again soon); false keeps w_hat in
+// the caches for a GEMM that follows immediately.
+template <int FMT, bool MX = false, bool STREAM = true>
 __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
   uint32_t byg, bxg;
   const TileDesc d = locate(a, byg, bxg);
   const uint32_t lane = threadIdx.x & 63;
   walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
-    if (t.full) fwd_tile<FMT, true, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
-    else fwd_tile<FMT, false, true, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    if (t.full) fwd_tile<FMT, true, STREAM, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    else fwd_tile<FMT, false, STREAM, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
   });
 }
 
@@ -241,8 +243,17 @@ __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict_
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, hipStream_t stream) {
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
+  if (keep && !mx) {
+    switch (fmt) {
+      case GWS_FMT_BF16: hipLaunchKernelGGL((sample_fwd_kernel<0, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      default: return GWS_ERR_FORMAT;
+    }
+    return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+  }
   if (mx) {
     switch (fmt) {
       case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;

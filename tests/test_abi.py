@@ -83,6 +83,10 @@ def test_argument_validation_launches_nothing(lib):
     wdesc = (_CTensor * 1)(_t(**base))
     assert lib.gws_linear_fwd(fake, 8, 32, 32, wdesc, 0, 1, 0, fake, 64, None) == SHAPE      # K mismatch
     assert lib.gws_linear_fwd(fake, 8, 64, 64, wdesc, 0, 9, 0, fake, 64, None) == FORMAT
+    assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, 4, None) == FORMAT    # no such mode
+    assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, -1, None) == FORMAT
+    assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, 1, None) == SHAPE     # sample-once needs 256-tiles
+    assert lib.gws_linear_fwd_mode(fake, 0, 64, 64, wdesc, 0, 1, 0, fake, 64, 3, None) == OK        # empty
     assert lib.gws_gemm_bf16(fake, 8, 48, 48, fake, 64, 64, 0, fake, 64, None) == SHAPE      # K % 32
     assert lib.gws_gemm_bf16(None, 8, 64, 64, fake, 64, 64, 0, fake, 64, None) == NULL
     assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty

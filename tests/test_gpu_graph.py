@@ -27,7 +27,8 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
         descs.append(gws.TensorDesc(rows=r, cols=c, seed=gws.gws_derive_seed(9, i), w=t["w"], w_hat=w_hat, bt=t["bt"],
                                     scale=scale, g=t["g"], dw=dw, dbt=dbt, ld=t["w"].stride(0)))
         outs += [w_hat, scale, dbt, dw]
-    # a linear whose shape selects the sample-once kernel when run eagerly
+    # a linear whose shape admits the sample-once kernel: asked for explicitly, it runs that kernel eagerly
+    # and records the two stateless kernels under capture
     M, K, N = 512, 256, 512
     x = synth.make_activation(710, M, K, device=DEV)
     tl = synth.make_tensor(711, K, N, bt=6.0, device=DEV, with_grad=False)
@@ -39,7 +40,7 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
     def run():
         gws.gws_sample_fwd(descs, fmt, step)
         gws.gws_sample_bwd(descs, step)
-        gws.gws_linear_fwd(x, dlin, y, fmt, step)
+        gws.gws_linear_fwd_mode(x, dlin, y, fmt, step, gws.LINEAR_SAMPLE_ONCE)
 
     run()                                      # eager reference (also the usual warm-up before a capture)
     torch.cuda.synchronize()

@@ -1,7 +1,8 @@
-"""GPU parity of gws_linear_fwd (sampling fused into the GEMM's weight operand) and of
-the plain twin gws_gemm_bf16, through the C ABI.
+"""GPU parity of gws_linear_fwd / gws_linear_fwd_mode (the sampled-weight linear in its three
+forms: sampling in the weight operand load, cooperative sample-once kernel, sampling kernel +
+plain GEMM) and of the plain twin gws_gemm_bf16, through the C ABI.
 
- - w_hat / scale written by the fused kernel: bit-exact against the oracle forward.
+ - w_hat / scale written by the call: bit-exact against the oracle forward.
  - Y against the oracle's fp64 GEMM on the oracle's w_hat: |y - ref| <= 2^-8 |ref| +
    K * 2^-24 * sum|x q| (one BF16 rounding plus fp32 accumulation in any order).
  - fused Y == plain GEMM on the separately sampled w_hat, bit for bit (same GEMM code).
@@ -36,7 +37,7 @@ def check_y(y_bits, x_bits, q_bits, w_is_nk, rows_sel=None):
     assert not bad.any(), (np.argwhere(bad)[:5], got[bad][:5], y64[bad][:5])
 
 
-def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, ldx_pad=0, ldy_pad=0):
+def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, ldx_pad=0, ldy_pad=0, mode=None):
     wr, wc = (N, K) if w_is_nk else (K, N)
     t = synth.make_tensor(200 + seed_id, wr, wc, bt=bt, with_grad=False)
     x_full = synth.make_activation(300 + seed_id, M, K + ldx_pad)
@@ -50,9 +51,12 @@ def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, l
     nbr, nbc = synth.n_blocks(wr, wc)
     scale = torch.zeros(nbr, nbc, dtype=torch.float32, device=DEV)
     desc = gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, w_hat=w_hat, bt=btd, scale=scale)
-    gws.gws_linear_fwd(x, desc, y, fmt, step, w_is_nk=w_is_nk)
+    if mode is None:
+        gws.gws_linear_fwd(x, desc, y, fmt, step, w_is_nk=w_is_nk)
+    else:
+        gws.gws_linear_fwd_mode(x, desc, y, fmt, step, mode, w_is_nk=w_is_nk)
     torch.cuda.synchronize()
-    # 1. sampled weight written by the fused kernel == oracle
+    # 1. sampled weight written by the call == oracle
     ref_q, ref_s = oracle.sample_fwd(synth.bits(t["w"]), t["bt"].numpy(), fmt, seed, step)
     assert (synth.bits(w_hat) == ref_q).all()
     assert (scale.cpu().numpy().view(np.uint32) == ref_s.view(np.uint32)).all()
@@ -81,10 +85,13 @@ def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, l
 @pytest.mark.parametrize("w_is_nk", [False, True])
 @pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
 def test_linear_small_shapes(w_is_nk, fmt):
-    run_case(128, 64, 128, w_is_nk, fmt, bt=6.0)
-    run_case(200, 96, 160, w_is_nk, fmt, seed_id=1)                 # ragged M, N not a tile multiple
+    run_case(128, 64, 128, w_is_nk, fmt, bt=6.0)                    # automatic choice: in-operand (M <= 128)
+    run_case(200, 96, 160, w_is_nk, fmt, seed_id=1)                 # two kernels; ragged M, N not a tile multiple
     run_case(37, 32, 32, w_is_nk, fmt, seed_id=2, step=3)
     run_case(300, 256, 416, w_is_nk, fmt, seed_id=3, ldx_pad=8, ldy_pad=16)
+    run_case(200, 96, 160, w_is_nk, fmt, seed_id=1, mode=gws.LINEAR_IN_OPERAND)
+    run_case(300, 256, 416, w_is_nk, fmt, seed_id=3, ldx_pad=8, ldy_pad=16, mode=gws.LINEAR_IN_OPERAND)
+    run_case(37, 32, 32, w_is_nk, fmt, seed_id=2, step=3, mode=gws.LINEAR_TWO_KERNELS)
 
 
 def test_plain_gemm_vs_fp64():
@@ -129,16 +136,38 @@ def test_plain_gemm_large_tile_path(w_is_nk):
 @pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
 def test_linear_sample_once_path(w_is_nk, fmt):
     # M, N multiples of 256, K of 64 and w_hat requested: cooperative sampling prologue + GEMM on w_hat
-    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2)
-    run_case(256, 64, 256, w_is_nk, fmt, bt=3.0, seed_id=8)
+    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2, mode=gws.LINEAR_SAMPLE_ONCE)
+    run_case(256, 64, 256, w_is_nk, fmt, bt=3.0, seed_id=8, mode=gws.LINEAR_SAMPLE_ONCE)
+    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2)        # automatic choice: two kernels, 256-tile GEMM
 
 
 def test_linear_sample_once_repeated_calls_reuse_the_sync_words():
     for step in range(4):
-        run_case(512, 192, 512, False, gws.FMT_FP8_E4M3, seed_id=9, step=step)
+        run_case(512, 192, 512, False, gws.FMT_FP8_E4M3, seed_id=9, step=step, mode=gws.LINEAR_SAMPLE_ONCE)
 
 
 def test_config5_fused_linear_8192x2048x5632_sampled_rows():
     M, K, N = 8192, 2048, 5632
     rows_sel = np.array([0, 1, 31, 127, 128, 4095, 4096, 8000, 8191])
-    run_case(M, K, N, False, gws.FMT_FP8_E4M3, bt=6.0, seed_id=5, rows_sel=rows_sel)
+    for mode in (None, gws.LINEAR_SAMPLE_ONCE, gws.LINEAR_IN_OPERAND):
+        run_case(M, K, N, False, gws.FMT_FP8_E4M3, bt=6.0, seed_id=5, rows_sel=rows_sel, mode=mode)
+
+
+def test_linear_mode_errors():
+    x = synth.make_activation(4, 200, 96).to(DEV)
+    t = synth.make_tensor(4, 96, 160, with_grad=False)
+    w, bt = t["w"].to(DEV), t["bt"].to(DEV)
+    y = torch.zeros(200, 160, dtype=torch.bfloat16, device=DEV)
+    full = gws.TensorDesc(rows=96, cols=160, seed=1, w=w, bt=bt, w_hat=torch.zeros_like(w), scale=torch.zeros(3, 5, device=DEV))
+    bare = gws.TensorDesc(rows=96, cols=160, seed=1, w=w, bt=bt)
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_fwd_mode(x, full, y, gws.FMT_FP8_E4M3, 0, gws.LINEAR_SAMPLE_ONCE)    # not a 256-tile shape
+    assert e.value.status == 2
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_fwd_mode(x, bare, y, gws.FMT_FP8_E4M3, 0, gws.LINEAR_TWO_KERNELS)    # nowhere to put w_hat
+    assert e.value.status == 1
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_fwd_mode(x, full, y, gws.FMT_FP8_E4M3, 0, 9)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert (synth.bits(y) == 0).all()                                                        # nothing was launched
