@@ -482,7 +482,10 @@ def linear_bench(torch, gws, synth, dev):
         gws.gws_linear_bwd_w(x, dy, d_bwd_plain, 0)
         gws.gws_sample_bwd(pk_bwd, 0)
 
+    dx = torch.empty_like(x)
     variants = {
+        "bwd_x": lambda: gws.gws_gemm_bf16(dy, w_hat, dx, w_is_nk=True),          # dX = dY * w_hat^T
+        "bwd_x_torch": lambda: torch.matmul(dy, w_hat.t(), out=dx),
         "bwd_w_fused": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd, 0),
         "bwd_w_plain": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd_plain, 0),
         "bwd_w_unfused": bwd_unfused,
@@ -521,6 +524,8 @@ def linear_bench(torch, gws, synth, dev):
             "unfused_torch_gemm_ms": t_unfused_torch, "sample_only_ms": t_sample,
             "plain_own_ms": t_plain, "plain_own_on_w_hat_ms": t_plain_what,
             "plain_torch_ms": t_torch, "plain_torch_on_w_hat_ms": t_torch_what,
+            "bwd_x": {"gemm_on_w_hat_ms": med["bwd_x"], "torch_matmul_ms": med["bwd_x_torch"],
+                      "TFLOPs": 2.0 * M * K * N / med["bwd_x"] / 1e9},
             "bwd_w": {"gemm_with_dbt_epilogue_ms": med["bwd_w_fused"], "gemm_plain_ms": med["bwd_w_plain"],
                       "gemm_plain_then_sample_bwd_ms": med["bwd_w_unfused"], "torch_matmul_ms": med["bwd_w_torch"],
                       "epilogue_overhead_pct": 100.0 * (med["bwd_w_fused"] - med["bwd_w_plain"]) / med["bwd_w_plain"],
