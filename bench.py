@@ -483,7 +483,18 @@ def linear_bench(torch, gws, synth, dev):
         gws.gws_sample_bwd(pk_bwd, 0)
 
     dx = torch.empty_like(x)
+    # eight layers in a row, as a forward pass issues them
+    def plain_loop(layers=8):
+        for _ in range(layers):
+            gws.gws_gemm_bf16(x, w, y)
+
+    def auto_loop(layers=8):
+        for l in range(layers):
+            gws.gws_linear_fwd(x, d_full, y, fmt, l)
+
     variants = {
+        "plain8": plain_loop,
+        "auto8": auto_loop,
         "bwd_x": lambda: gws.gws_gemm_bf16(dy, w_hat, dx, w_is_nk=True),          # dX = dY * w_hat^T
         "bwd_x_torch": lambda: torch.matmul(dy, w_hat.t(), out=dx),
         "bwd_w_fused": lambda: gws.gws_linear_bwd_w(x, dy, d_bwd, 0),
@@ -524,6 +535,8 @@ def linear_bench(torch, gws, synth, dev):
             "unfused_torch_gemm_ms": t_unfused_torch, "sample_only_ms": t_sample,
             "plain_own_ms": t_plain, "plain_own_on_w_hat_ms": t_plain_what,
             "plain_torch_ms": t_torch, "plain_torch_on_w_hat_ms": t_torch_what,
+            "eight_layers": {"plain_gemm_ms_per_layer": med["plain8"] / 8, "linear_fwd_ms_per_layer": med["auto8"] / 8,
+                             "linear_fwd_overhead_pct": 100.0 * (med["auto8"] - med["plain8"]) / med["plain8"]},
             "bwd_x": {"gemm_on_w_hat_ms": med["bwd_x"], "torch_matmul_ms": med["bwd_x_torch"],
                       "TFLOPs": 2.0 * M * K * N / med["bwd_x"] / 1e9},
             "bwd_w": {"gemm_with_dbt_epilogue_ms": med["bwd_w_fused"], "gemm_plain_ms": med["bwd_w_plain"],

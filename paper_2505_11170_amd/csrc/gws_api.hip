@@ -101,6 +101,11 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   uint32_t per_wg = 1, per_x = 1;
   if (!fwd)
     while (per_x < 4 && total / (per_x + 1) >= 3000) ++per_x;
+  // Forward stores: a call that writes little (one weight, a few layers) is usually followed by its
+  // consumer, and the whole of w_hat fits in the last-level cache, so it is written with ordinary
+  // stores; a call over a model's worth of weights streams past the caches (non-temporal stores).
+  // A workgroup tile is 32 x 256 elements = 16 KiB of w_hat.
+  if (fwd && total * (16u << 10) <= (32u << 20)) keep = true;
 
   LaunchArgs a;
   memset(&a, 0, sizeof a);
