@@ -171,3 +171,25 @@ def test_linear_mode_errors():
     assert e.value.status == 4
     torch.cuda.synchronize()
     assert (synth.bits(y) == 0).all()                                                        # nothing was launched
+
+
+def test_large_tile_gemm_random_shapes_and_strides():
+    # the 256x256x64 tile at seeded random shapes: odd and even numbers of K-steps (1 .. 11), padded
+    # leading dimensions, both weight layouts; every element against the fp64 GEMM
+    rng = np.random.default_rng(2505)
+    for case in range(10):
+        M, N = 256 * int(rng.integers(1, 4)), 256 * int(rng.integers(1, 4))
+        K = 64 * int(rng.integers(1, 12))
+        w_is_nk = bool(case & 1)
+        padx, padw, pady = (8 * int(rng.integers(0, 3)) for _ in range(3))
+        x_full = synth.make_activation(400 + case, M, K + padx).to(DEV)
+        wr, wc = (N, K) if w_is_nk else (K, N)
+        w_full = synth.make_tensor(400 + case, wr, wc + padw, with_grad=False)["w"].to(DEV)
+        y_full = torch.zeros(M, N + pady, dtype=torch.bfloat16, device=DEV)
+        x, w, y = x_full[:, :K], w_full[:, :wc], y_full[:, :N]
+        gws.gws_gemm_bf16(x, w, y, w_is_nk=w_is_nk)
+        torch.cuda.synchronize()
+        xb = np.ascontiguousarray(synth.bits(x_full)[:, :K])
+        wb = np.ascontiguousarray(synth.bits(w_full)[:, :wc])
+        check_y(np.ascontiguousarray(synth.bits(y_full)[:, :N]), xb, wb, w_is_nk)
+        assert (synth.bits(y_full)[:, N:] == 0).all(), (case, "padding of Y written")

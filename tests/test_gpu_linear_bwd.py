@@ -105,3 +105,12 @@ def test_shape_and_argument_errors():
         gws.gws_linear_bwd_w(x, dy, gws.TensorDesc(rows=256, cols=256, seed=1, dw=x), 0)   # dW on top of X
     assert e.value.status == 6
     torch.cuda.synchronize()
+
+
+def test_random_shapes():
+    # seeded random weight shapes (multiples of 256) and token counts (multiples of 64: 1 .. 9 K-steps)
+    rng = np.random.default_rng(1117)
+    for case in range(6):
+        K, N = 256 * int(rng.integers(1, 4)), 256 * int(rng.integers(1, 4))
+        M = 64 * int(rng.integers(1, 10))
+        run_case(M, K, N, bool(case & 1), 830 + 2 * case, pad=8 * int(rng.integers(0, 3)))
