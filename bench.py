@@ -28,7 +28,7 @@ EVENT_EVERY = 4             # steps between event-bracketed steps in the timed r
 # HBM bytes per sample_fwd_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (KiB per dispatch, FETCH_SIZE x 2.0 and WRITE_SIZE x 1.0: the factors a 1 GiB plain device
 # copy gives in the same runs).  Summaries: profiles/sample_kernels_<workload>.md.
-MEASURED_FWD_TRAFFIC_BYTES = {"gpt2_124m": 341616605, "llama_1b": 1298414761}
+MEASURED_FWD_TRAFFIC_BYTES = {"gpt2_124m": 341658204, "llama_1b": 1298448672}
 
 
 def parse():
