@@ -484,6 +484,27 @@ def linear_bench(torch, gws, synth, dev):
 
     dx = torch.empty_like(x)
     # eight layers in a row, as a forward pass issues them
+    # ... and with the sampling of the next layer's weight riding in the GEMM's launch (two w_hat buffers)
+    w_hat_b, scale_b = torch.empty_like(w_hat), torch.empty_like(scale)
+    whs = (w_hat, w_hat_b)
+    nxt = [gws.TensorDesc(rows=K, cols=N, seed=seed, w=w, w_hat=wh, bt=bt, scale=sc)
+           for wh, sc in ((w_hat, scale), (w_hat_b, scale_b))]
+
+    # a smaller next weight (the 1B model's 2048 x 2048 projections): its sampling fits beside the GEMM's last round
+    tq = synth.make_tensor(7, 2048, 2048, bt=6.0, device=dev, with_grad=False)
+    d_q = gws.TensorDesc(rows=2048, cols=2048, seed=seed, w=tq["w"], w_hat=torch.empty_like(tq["w"]), bt=tq["bt"],
+                         scale=torch.empty(64, 64, device=dev))
+    pk_q = gws.pack([d_q])
+
+    def gemm_then_sample_q():
+        gws.gws_gemm_bf16(x, w_hat, y)
+        gws.gws_sample_fwd(pk_q, fmt, 1)
+
+    def next_loop(layers=8):
+        gws.gws_sample_fwd(pk, fmt, 0)                                   # the first layer's weight
+        for l in range(layers):
+            gws.gws_gemm_bf16_sample_next(x, whs[l % 2], y, nxt[(l + 1) % 2], fmt, l + 1)
+
     def plain_loop(layers=8):
         for _ in range(layers):
             gws.gws_gemm_bf16(x, w, y)
@@ -494,6 +515,10 @@ def linear_bench(torch, gws, synth, dev):
 
     variants = {
         "plain8": plain_loop,
+        "next8": next_loop,
+        "gemm_next": lambda: gws.gws_gemm_bf16_sample_next(x, w_hat, y, nxt[1], fmt, 1),
+        "gemm_next_q": lambda: gws.gws_gemm_bf16_sample_next(x, w_hat, y, d_q, fmt, 1),
+        "gemm_then_q": gemm_then_sample_q,
         "auto8": auto_loop,
         "bwd_x": lambda: gws.gws_gemm_bf16(dy, w_hat, dx, w_is_nk=True),          # dX = dY * w_hat^T
         "bwd_x_torch": lambda: torch.matmul(dy, w_hat.t(), out=dx),
@@ -536,7 +561,16 @@ def linear_bench(torch, gws, synth, dev):
             "plain_own_ms": t_plain, "plain_own_on_w_hat_ms": t_plain_what,
             "plain_torch_ms": t_torch, "plain_torch_on_w_hat_ms": t_torch_what,
             "eight_layers": {"plain_gemm_ms_per_layer": med["plain8"] / 8, "linear_fwd_ms_per_layer": med["auto8"] / 8,
-                             "linear_fwd_overhead_pct": 100.0 * (med["auto8"] - med["plain8"]) / med["plain8"]},
+                             "linear_fwd_overhead_pct": 100.0 * (med["auto8"] - med["plain8"]) / med["plain8"],
+                             "gemm_sample_next_ms_per_layer": med["next8"] / 8,
+                             "gemm_sample_next_overhead_pct": 100.0 * (med["next8"] - med["plain8"]) / med["plain8"],
+                             "note": "gemm_sample_next: one gws_sample_fwd for the first layer, then per layer one "
+                                     "gws_gemm_bf16_sample_next (GEMM on w_hat of layer l, sampling of layer l+1 in the same launch)"},
+            "gemm_sample_next": {"same_shape_next_ms": med["gemm_next"], "next_2048x2048_riding_ms": med["gemm_next_q"],
+                                 "gemm_then_sample_2048x2048_ms": med["gemm_then_q"], "gemm_on_w_hat_alone_ms": t_plain_what,
+                                 "note": "a 2048 x 5632 next weight does not fit beside the last round of tiles (64 of 256 compute "
+                                         "units idle, one wavefront per SIMD) and is sampled by a second launch; a 2048 x 2048 one rides "
+                                         "in the GEMM's launch"},
             "bwd_x": {"gemm_on_w_hat_ms": med["bwd_x"], "torch_matmul_ms": med["bwd_x_torch"],
                       "TFLOPs": 2.0 * M * K * N / med["bwd_x"] / 1e9},
             "bwd_w": {"gemm_with_dbt_epilogue_ms": med["bwd_w_fused"], "gemm_plain_ms": med["bwd_w_plain"],

@@ -212,6 +212,20 @@ int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx,
                   const void* w, int64_t N, int64_t ldw, int w_is_nk,
                   void* y, int64_t ldy, void* stream);
 
+/* gws_gemm_bf16 with the forward sampling of another weight riding along: Y = X * W as above (W is
+ * typically a w_hat sampled earlier), and `next` (one host descriptor, may be NULL) is sampled as
+ * gws_sample_fwd(next, 1, fmt, step) would: next->w_hat and next->scale are written.  This is how a
+ * forward pass that knows its layers hides the sampling of layer l+1 behind the GEMM of layer l
+ * (the paper keeps sampling and matmul in separate kernels, Sec. 3.5; so does this, in one launch):
+ * when the GEMM takes the 256-tile kernel and its last round of tiles leaves compute units idle,
+ * that many extra workgroups of the same launch do the sampling there; otherwise the sampling kernel
+ * is launched after the GEMM.  Same bytes either way; no state; next->w_hat must not overlap x, w
+ * or y (GWS_ERR_ALIAS).                                                                        */
+int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx,
+                              const void* w, int64_t N, int64_t ldw, int w_is_nk,
+                              void* y, int64_t ldy,
+                              const gws_tensor* next, int fmt, uint64_t step, void* stream);
+
 /* Measurement aid: copies w to w_hat for n tensors with the launch shape, loads and
  * stores of gws_sample_fwd and none of its arithmetic.  Its rate is the ceiling the
  * memory system sets for that access pattern, against which the forward pass is read.

@@ -18,7 +18,7 @@ FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 LINEAR_AUTO, LINEAR_SAMPLE_ONCE, LINEAR_IN_OPERAND, LINEAR_TWO_KERNELS = 0, 1, 2, 3
 
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode", "gws_linear_bwd_w",
-           "gws_gemm_bf16", "gws_copy_tiles", "gws_block_absmax", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
+           "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_copy_tiles", "gws_block_absmax", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
 
 
 class GwsError(RuntimeError):
@@ -113,6 +113,8 @@ def load_library() -> ctypes.CDLL:
     L.gws_linear_fwd.restype = ci
     L.gws_linear_fwd_mode.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, ci, vp]
     L.gws_linear_fwd_mode.restype = ci
+    L.gws_gemm_bf16_sample_next.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, tp, ci, u64, vp]
+    L.gws_gemm_bf16_sample_next.restype = ci
     L.gws_copy_tiles.argtypes = [tp, ci, vp]
     L.gws_copy_tiles.restype = ci
     L.gws_block_absmax.argtypes = [tp, ci, vp]
@@ -307,6 +309,17 @@ def gws_gemm_bf16(x, w, y, w_is_nk: bool = False, stream=None) -> None:
     N = int(w.shape[0] if w_is_nk else w.shape[1])
     _check(L.gws_gemm_bf16(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
                            _p(y), int(y.stride(0)), _stream(stream)), "gws_gemm_bf16")
+
+
+def gws_gemm_bf16_sample_next(x, w, y, nxt: Optional[TensorDesc], fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:
+    """``gws_gemm_bf16`` with ``gws_sample_fwd([nxt], fmt, step)`` riding along in the same launch where that pays."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    N = int(w.shape[0] if w_is_nk else w.shape[1])
+    arr = None if nxt is None else _marshal([nxt])
+    _check(L.gws_gemm_bf16_sample_next(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
+                                       _p(y), int(y.stride(0)), arr, int(fmt), int(step), _stream(stream)),
+           "gws_gemm_bf16_sample_next")
 
 
 def gws_copy_tiles(t: Sequence[TensorDesc], stream=None) -> None:

@@ -381,6 +381,64 @@ int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* 
   return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
 }
 
+int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                              int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int fmt, uint64_t step,
+                              void* stream) {
+  if (!next) return gws_gemm_bf16(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, stream);
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  int rc = check_fwd(*next);
+  if (rc != GWS_OK) return rc;
+  // the GEMM's own argument rules (as gws_gemm_bf16), checked before anything is launched
+  if (M < 0 || K < 0 || N < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  const bool gemm_empty = (M == 0 || N == 0);
+  if (!gemm_empty) {
+    if ((K & 31) != 0 || (N & 31) != 0 || K == 0) return GWS_ERR_SHAPE;
+    const int64_t wcols = w_is_nk ? K : N;
+    if (ldx < K || ldy < N || ldw < wcols || ((ldx | ldy | ldw) & 7) != 0 ||
+        ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31 || ldw >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+    if (!x || !w || !y) return GWS_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return GWS_ERR_ALIGN;
+    // the sampled weight must not be an operand or the result of this GEMM
+    const size_t hat_bytes = (size_t)next->rows * next->ld * 2;
+    if (next->rows > 0 && next->cols > 0 &&
+        (overlap2(next->w_hat, hat_bytes, w, (size_t)(w_is_nk ? N : K) * ldw * 2) ||
+         overlap2(next->w_hat, hat_bytes, x, (size_t)M * ldx * 2) || overlap2(next->w_hat, hat_bytes, y, (size_t)M * ldy * 2)))
+      return GWS_ERR_ALIAS;
+  }
+  const bool next_empty = (next->rows == 0 || next->cols == 0);
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.x = (const uint16_t*)x; g.w = (const uint16_t*)w; g.y = (uint16_t*)y;
+  g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
+  g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)ldw; g.ldy = (uint32_t)ldy;
+  // Ride along when the 256-tile GEMM leaves compute units without a tile in its last round and the
+  // sampling fits beside that round: measured, a riding wavefront (one per SIMD, the GEMM's register
+  // allocation, beside the GEMM's memory traffic) takes about 3.8 us per 32 x 64 tile, a GEMM tile
+  // about 1.6 us per K-step of 64.
+  if (!gemm_empty && !next_empty && gemm256_applicable(g) && (next->rows & 31) == 0 && (next->cols & 63) == 0) {
+    const int cus = compute_units();
+    const uint64_t tiles = (uint64_t)(M / 256) * (uint64_t)(N / 256);
+    const uint32_t idle = cus > 0 ? (uint32_t)((cus - tiles % cus) % cus) : 0u;
+    if (idle > 0) {
+      const double units = (double)(next->rows / 32) * (double)(next->cols / 64);     // wavefront tiles
+      const double t_sample_us = units / (4.0 * idle) * 3.8, t_tile_us = (double)(K / 64) * 1.6 + 5.0;
+      if (t_sample_us <= 0.6 * t_tile_us) {   // with a margin: a riding part that outlasts the tiles costs more than a launch
+        TileDesc d;
+        memset(&d, 0, sizeof d);
+        d.p0 = next->w; d.p1 = next->w_hat; d.p2 = (void*)next->bt; d.p3 = next->scale; d.p4 = nullptr;
+        fill_common(d, *next, 1);
+        d.b_target = 0.0f; d.b_delta = 1.0f; d.lambda_m = 0.0f;
+        return launch_gemm256_ride(g, w_is_nk, d, fmt, step, idle, (hipStream_t)stream);
+      }
+    }
+  }
+  if (!gemm_empty) {
+    rc = launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(next, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, /*keep=*/true);
+}
+
 // Philox4x32-10 on the host, for the seed derivation only.
 uint64_t gws_derive_seed(uint64_t user_seed, uint64_t tensor_id) {
   uint32_t c0 = (uint32_t)tensor_id, c1 = (uint32_t)(tensor_id >> 32), c2 = 0x47575331u, c3 = 0u;
@@ -407,6 +465,6 @@ const char* gws_status_string(int status) {
   }
 }
 
-int gws_version(void) { return 5; }
+int gws_version(void) { return 6; }
 
 }  // extern "C"

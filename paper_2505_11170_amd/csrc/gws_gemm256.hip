@@ -94,10 +94,9 @@ __device__ __forceinline__ bool grid_arrive_and_wait(uint32_t epoch) {
 // kDepth tiles is loaded before the first is computed, so the single wavefront per
 // SIMD pays the memory latency once per batch; neighbouring wavefronts take
 // neighbouring tiles, so a workgroup reads 512 contiguous bytes per row.
-template <int FMT>
-__device__ __forceinline__ void sample_tiles(const GemmArgs& g, const TileDesc& d, uint32_t first, uint32_t stride,
-                                             uint32_t lane) {
-  constexpr int kDepth = 3;
+template <int FMT, int kDepth = 3>
+__device__ __forceinline__ void sample_tiles(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, uint32_t first,
+                                             uint32_t stride, uint32_t lane) {
   const uint32_t per_row = d.cols >> 6, ntiles = (d.rows >> 5) * per_row;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   for (uint32_t base = first; base < ntiles; base += kDepth * stride) {
@@ -115,7 +114,7 @@ __device__ __forceinline__ void sample_tiles(const GemmArgs& g, const TileDesc& 
       const uint32_t id = base + j * stride;
       if (id < ntiles) {
         const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
-        fwd_tile<FMT, true, false>(g.step_lo, g.step_hi, d, t[j], by, cb, lane);
+        fwd_tile<FMT, true, false>(step_lo, step_hi, d, t[j], by, cb, lane);
       }
     }
   }
@@ -133,12 +132,12 @@ __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs 
   d.row0 = g.row0; d.cg0 = g.cg0; d.seed_lo = g.seed_lo; d.seed_hi = g.seed_hi; d.tiles_x = 0;
 
   // ---- phase 1: sample W once, all wavefronts of the grid ----
-  sample_tiles<FMT>(g, d, blockIdx.x * 4 + wave, gridDim.x * 4, lane);
+  sample_tiles<FMT>(g.step_lo, g.step_hi, d, blockIdx.x * 4 + wave, gridDim.x * 4, lane);
   __syncthreads();
   if (tid == 0) gave_up = grid_arrive_and_wait(epoch) ? 0u : 1u;
   __syncthreads();
   if (gave_up) {  // not every workgroup arrived in time: sample everything here (same bytes)
-    sample_tiles<FMT>(g, d, wave, 4, lane);
+    sample_tiles<FMT>(g.step_lo, g.step_hi, d, wave, 4, lane);
     __threadfence();
     __syncthreads();
   }
@@ -149,6 +148,54 @@ __global__ __launch_bounds__(256, 1) void linear256_fused_kernel(const GemmArgs 
     gemm256_tile<W_NK>(g, g.w_hat, L);
     __syncthreads();  // the epilogue staging is read before the next tile's loads overwrite it
   }
+}
+
+// Plain GEMM with the forward sampling of another weight riding along: the grid is the GEMM's tiles
+// followed by `gridDim.x - tiles` more workgroups, which start when compute units run out of tiles (the
+// last, partly empty round) and sample the weight `d` (32 x 64 wavefront tiles, as above) while the last
+// tiles finish.  The two halves share nothing: no synchronisation, no state.
+template <int FMT, bool W_NK>
+__global__ __launch_bounds__(256, 1) void gemm256_ride_kernel(const GemmArgs g, const TileDesc d, const uint32_t step_lo,
+                                                              const uint32_t step_hi, const uint32_t tiles) {
+  if (blockIdx.x < tiles) {
+    gemm256_tile<W_NK>(g, g.w, blockIdx.x);
+  } else {
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    sample_tiles<FMT, 8>(step_lo, step_hi, d, (blockIdx.x - tiles) * 4 + wave, (gridDim.x - tiles) * 4, lane);
+  }
+}
+
+template <int FMT>
+static int launch_ride_fmt(const GemmArgs& g, int w_is_nk, const TileDesc& d, uint32_t step_lo, uint32_t step_hi,
+                           uint32_t tiles, uint32_t extra, hipStream_t s) {
+  if (w_is_nk)
+    hipLaunchKernelGGL((gemm256_ride_kernel<FMT, true>), dim3(tiles + extra), dim3(256), 0, s, g, d, step_lo, step_hi, tiles);
+  else
+    hipLaunchKernelGGL((gemm256_ride_kernel<FMT, false>), dim3(tiles + extra), dim3(256), 0, s, g, d, step_lo, step_hi, tiles);
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+int launch_gemm256_ride(const GemmArgs& g, int w_is_nk, const TileDesc& d, int fmt, uint64_t step, uint32_t extra,
+                        hipStream_t stream) {
+  const uint64_t tiles = (uint64_t)(g.M / g256::TM) * (g.N / g256::TN);
+  if (tiles + extra >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
+  const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+  switch (fmt) {
+    case GWS_FMT_BF16: return launch_ride_fmt<0>(g, w_is_nk, d, lo, hi, (uint32_t)tiles, extra, stream);
+    case GWS_FMT_FP8_E4M3: return launch_ride_fmt<1>(g, w_is_nk, d, lo, hi, (uint32_t)tiles, extra, stream);
+    case GWS_FMT_FP6_E3M2: return launch_ride_fmt<2>(g, w_is_nk, d, lo, hi, (uint32_t)tiles, extra, stream);
+    default: return GWS_ERR_FORMAT;
+  }
+}
+
+int compute_units() {
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return n;
+  }();
+  return cus;
 }
 
 bool gemm256_applicable(const GemmArgs& g) {
@@ -176,12 +223,7 @@ bool linear256_fused_applicable(const GemmArgs& g) {
 
 int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream) {
   // one workgroup per compute unit: the whole grid is resident, so the arrival counter completes
-  static const int cus = [] {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    return n;
-  }();
+  const int cus = compute_units();
   if (cus <= 0) return GWS_ERR_LAUNCH;
   static std::atomic<uint32_t> next_epoch{1};
   uint32_t epoch = next_epoch.fetch_add(1);

@@ -81,6 +81,11 @@ constexpr int kFusedSampleOnce = 1, kFusedInOperand = 2;
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
+// the 256-tile GEMM followed, in the same grid, by `extra` workgroups that sample the weight `d`
+// (rows a multiple of 32, columns of 64) as the forward pass does
+int launch_gemm256_ride(const GemmArgs& g, int w_is_nk, const TileDesc& d, int fmt, uint64_t step, uint32_t extra,
+                        hipStream_t stream);
+int compute_units();   // of the current device; 0 if the query fails
 bool linear256_fused_applicable(const GemmArgs& g);
 int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream);
 // Weight-gradient GEMM (gws_gemm256_tn.hip): y[M x N] = x^T * w with x [K x M], w [K x N]

@@ -90,6 +90,16 @@ def test_argument_validation_launches_nothing(lib):
     assert lib.gws_gemm_bf16(fake, 8, 48, 48, fake, 64, 64, 0, fake, 64, None) == SHAPE      # K % 32
     assert lib.gws_gemm_bf16(None, 8, 64, 64, fake, 64, 64, 0, fake, 64, None) == NULL
     assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty
+    # GEMM with the next weight's sampling: the next weight is checked like gws_sample_fwd's, and may not
+    # overlap the GEMM's operands
+    nxt = (_CTensor * 1)(_t(**base))
+    gemm = (fake, 256, 64, 64, fake + 0x400000, 256, 256, 0, fake + 0x800000, 256)
+    assert lib.gws_gemm_bf16_sample_next(*gemm, nxt, 9, 0, None) == FORMAT
+    assert lib.gws_gemm_bf16_sample_next(*gemm, (_CTensor * 1)(_t(**{**base, "bt": None})), 1, 0, None) == NULL
+    assert lib.gws_gemm_bf16_sample_next(*gemm, (_CTensor * 1)(_t(**{**base, "w_hat": fake + 0x400000})), 1, 0, None) == ALIAS
+    assert lib.gws_gemm_bf16_sample_next(*gemm, (_CTensor * 1)(_t(**{**base, "w_hat": fake + 0x800040})), 1, 0, None) == ALIAS
+    assert lib.gws_gemm_bf16_sample_next(fake, 256, 48, 48, fake + 0x400000, 256, 256, 0, fake + 0x800000, 256, nxt, 1, 0, None) == SHAPE
+    assert lib.gws_gemm_bf16_sample_next(None, 256, 64, 64, fake + 0x400000, 256, 256, 0, fake + 0x800000, 256, nxt, 1, 0, None) == NULL
     for s in range(7):
         assert lib.gws_status_string(s)
 

@@ -193,3 +193,54 @@ def test_large_tile_gemm_random_shapes_and_strides():
         wb = np.ascontiguousarray(synth.bits(w_full)[:, :wc])
         check_y(np.ascontiguousarray(synth.bits(y_full)[:, :N]), xb, wb, w_is_nk)
         assert (synth.bits(y_full)[:, N:] == 0).all(), (case, "padding of Y written")
+
+
+def run_next_case(M, K, N, w_is_nk, next_rows, next_cols, fmt, idx, step=3, next_pad=0, rows_sel=None):
+    """gws_gemm_bf16_sample_next: Y against the fp64 GEMM, the riding forward pass against the oracle."""
+    x = synth.make_activation(500 + idx, M, K).to(DEV)
+    wr, wc = (N, K) if w_is_nk else (K, N)
+    w = synth.make_tensor(500 + idx, wr, wc, with_grad=False)["w"].to(DEV)
+    y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    t = synth.make_tensor(600 + idx, next_rows, next_cols, ld=next_cols + next_pad, with_grad=False)
+    nw, nbt = t["w"].to(DEV), t["bt"].to(DEV)
+    n_hat = nw.clone()                                     # padding columns must keep these bytes
+    nbr, nbc = synth.n_blocks(next_rows, next_cols)
+    n_scale = torch.full((nbr, nbc), float("nan"), device=DEV)
+    seed = oracle.derive_seed(7, idx)
+    nxt = gws.TensorDesc(rows=next_rows, cols=next_cols, ld=next_cols + next_pad, seed=seed, w=nw, w_hat=n_hat, bt=nbt, scale=n_scale)
+    gws.gws_gemm_bf16_sample_next(x, w, y, nxt, fmt, step, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y), synth.bits(x), synth.bits(w), w_is_nk, rows_sel)
+    ref_q, ref_s = oracle.sample_fwd(synth.bits(t["w"]), t["bt"].numpy(), fmt, seed, step, cols=next_cols)
+    assert (synth.bits(n_hat) == ref_q).all(), ("w_hat of the next weight", idx)
+    assert (n_scale.cpu().numpy().view(np.uint32) == ref_s.view(np.uint32)).all(), ("scale of the next weight", idx)
+    return y
+
+
+@pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
+def test_gemm_with_the_next_weight_sampled_alongside(fmt):
+    run_next_case(768, 192, 1280, False, 128, 320, fmt, 0)                   # 15 tiles: the sampling rides in the same launch
+    run_next_case(512, 128, 512, True, 256, 1024, fmt, 1, next_pad=8)        # [N x K] weight, padded next weight
+    run_next_case(768, 192, 1280, False, 96, 300, fmt, 2, next_pad=4)        # ragged next weight: separate launch
+    run_next_case(200, 96, 160, False, 128, 320, fmt, 3)                     # GEMM not on the large tile: separate launch
+    run_next_case(256, 64, 256, False, 4096, 4096, fmt, 4)                   # sampling far longer than the GEMM: separate launch
+
+
+def test_gemm_next_without_idle_compute_units_and_without_next():
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert cus % 16 == 0
+    M, N = 256 * 16, 256 * (cus // 16)                                       # exactly one tile per compute unit
+    y = run_next_case(M, 64, N, False, 128, 320, gws.FMT_FP8_E4M3, 5, rows_sel=np.array([0, 255, 256, M - 1]))
+    # next = None is the plain GEMM
+    x = synth.make_activation(505, M, 64).to(DEV)
+    w = synth.make_tensor(505, 64, N, with_grad=False)["w"].to(DEV)
+    y2 = torch.zeros_like(y)
+    gws.gws_gemm_bf16_sample_next(x, w, y2, None, gws.FMT_FP8_E4M3, 0)
+    torch.cuda.synchronize()
+    assert (synth.bits(y2) == synth.bits(y)).all()
+
+
+def test_config5_gemm_with_the_next_weight_sampled_alongside():
+    rows_sel = np.array([0, 1, 127, 128, 4095, 4096, 8191])
+    run_next_case(8192, 2048, 5632, False, 2048, 5632, gws.FMT_FP8_E4M3, 6, rows_sel=rows_sel)   # too much to ride: two launches
+    run_next_case(8192, 2048, 5632, False, 2048, 2048, gws.FMT_FP8_E4M3, 7, rows_sel=rows_sel)   # rides beside the last round of tiles
