@@ -36,11 +36,18 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
     y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
     dlin = gws.TensorDesc(rows=K, cols=N, seed=5, w=tl["w"], w_hat=lw_hat, bt=tl["bt"], scale=lscale)
     outs += [lw_hat, lscale, y]
+    # the plain GEMM with the sampling of another weight riding in its launch
+    y2 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    tn = synth.make_tensor(712, 768, 768, device=DEV, with_grad=False)
+    n_hat, n_scale = torch.zeros_like(tn["w"]), torch.zeros(24, 24, device=DEV)
+    dnext = gws.TensorDesc(rows=768, cols=768, seed=6, w=tn["w"], w_hat=n_hat, bt=tn["bt"], scale=n_scale)
+    outs += [y2, n_hat, n_scale]
 
     def run():
         gws.gws_sample_fwd(descs, fmt, step)
         gws.gws_sample_bwd(descs, step)
         gws.gws_linear_fwd_mode(x, dlin, y, fmt, step, gws.LINEAR_SAMPLE_ONCE)
+        gws.gws_gemm_bf16_sample_next(x, tl["w"], y2, dnext, fmt, step)
 
     run()                                      # eager reference (also the usual warm-up before a capture)
     torch.cuda.synchronize()
