@@ -101,12 +101,14 @@ __device__ __forceinline__ void sample_tiles(uint32_t step_lo, uint32_t step_hi,
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   for (uint32_t base = first; base < ntiles; base += kDepth * stride) {
     Tile t[kDepth];
+    float bv[kDepth];   // the lane's block parameter, fetched with the tile instead of once the tile is reduced
 #pragma unroll
     for (int j = 0; j < kDepth; ++j) {
       const uint32_t id = base + j * stride;
       if (id < ntiles) {
         const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
         t[j] = load_tile(global_ptr<uint16_t>(d.p0), d, by, cb, cb + gc * 8, r0);
+        bv[j] = global_ptr<float>(d.p2)[(size_t)by * (d.cols >> 5) + (cb >> 5) + (gc >> 2)];
       }
     }
 #pragma unroll
@@ -114,7 +116,7 @@ __device__ __forceinline__ void sample_tiles(uint32_t step_lo, uint32_t step_hi,
       const uint32_t id = base + j * stride;
       if (id < ntiles) {
         const uint32_t by = id / per_row, cb = (id - by * per_row) * 64;
-        fwd_tile<FMT, true, false>(step_lo, step_hi, d, t[j], by, cb, lane);
+        fwd_tile<FMT, true, false, false, true>(step_lo, step_hi, d, t[j], by, cb, lane, bv[j]);
       }
     }
   }

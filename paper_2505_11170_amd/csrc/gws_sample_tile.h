@@ -104,9 +104,11 @@ __device__ __forceinline__ void store_codes(GWS_GLOBAL uint8_t* row, uint32_t co
 // that is not consumed at once; off, the stores stay in cache for a reader that follows.
 // MX: the output is element codes (p1, row stride ldc) and E8M0 block scales (p4)
 // instead of the BF16 container.
-template <int FMT, bool FULL, bool STREAM = true, bool MX = false>
+// BT_PRE: the caller has already fetched this lane's block parameter (bt_pre), as a wavefront that works
+// through several tiles alone does together with the tile loads, so that its latency is not paid per tile.
+template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false>
 __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
-                                         uint32_t by, uint32_t col_base, uint32_t lane) {
+                                         uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f) {
   const uint32_t row_base = by * 32;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   const uint32_t col = col_base + gc * 8;
@@ -131,7 +133,7 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   const uint32_t nbc = (d.cols + 31) >> 5;
   const uint32_t bcol = (col_base >> 5) + (gc >> 2);
   const bool block_exists = FULL || bcol < nbc;
-  const float bv = block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f;
+  const float bv = BT_PRE ? bt_pre : (block_exists ? bt[(size_t)by * nbc + bcol] : 0.0f);
   // Eq. 11 (the product and the sum rounded separately); identity for a plain b_t
   const float btv = __fadd_rn(d.b_target, __fmul_rn(bv, d.b_delta));
   BlockScale b = block_scale(a16, btv);
