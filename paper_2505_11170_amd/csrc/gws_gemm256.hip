@@ -1,8 +1,8 @@
 // Large-tile BF16 MFMA GEMM for gfx950: Y[M x N] = X[M x K] * W, W stored [K x N] or
 // [N x K].  Used when M, N are multiples of 256 and K of 64.  The tile itself (direct
 // global -> LDS loads, swizzled stages, pinned MFMA / LDS-read / load interleave) is in
-// gws_gemm256_core.h; here are the tile numbering, the plain kernel and the fused
-// sample-once kernel.
+// gws_gemm256_core.h; here are the plain kernel, the fused sample-once kernel and the
+// plain kernel with another weight's sampling riding at the end of its grid.
 // Tiles are numbered so that the 32 workgroups running together on one XCD
 // (workgroups are dealt round-robin to the 8 XCDs, each with its own L2) form an
 // 8 x 4 patch that shares 8 X panels and 4 W panels.
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const GemmArgs g) {
 // ---------------------------------------------------------------------------
 // Fused sampled-weight linear, sample-once form.  A persistent grid (one
 // workgroup per compute unit) first samples W cooperatively: every wavefront
-// takes 32x32 blocks of the stored matrix round-robin (paper Eq. 3 + cast, as in
+// takes 32x64 tiles of the stored matrix round-robin (paper Eq. 3 + cast, as in
 // the forward kernel), writes w_hat and scale, and the grid meets at one
 // device-wide arrival counter.  The tiles of the GEMM then read w_hat through
 // L2 like a plain weight.  Each block is sampled once, instead of once per
