@@ -3,9 +3,9 @@
  *
  * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
  * every other pointer is host memory.  The library allocates no device memory,
- * keeps no global state (one exception is stated at gws_linear_fwd_mode) and is
- * thread-safe.  All GPU work is enqueued asynchronously on the given stream (a
- * hipStream_t passed as void*, NULL = the default stream); no call synchronises.
+ * keeps no global state and is thread-safe.  All GPU work is enqueued
+ * asynchronously on the given stream (a hipStream_t passed as void*, NULL = the
+ * default stream); no call synchronises.
  * The return value is a gws_status and reports argument and launch errors only;
  * on any error nothing has been launched for the failing call.
  *
@@ -26,6 +26,7 @@
 #ifndef GWS_H
 #define GWS_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -162,23 +163,17 @@ int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, 
  *   y : device BF16 [M x N], leading dimension ldy; fp32 accumulation, one
  *       round-to-nearest-even to BF16.
  * K and N must be multiples of 32; ldx, ldy multiples of 8.
- * Three ways to the same bytes (w_hat, scale and Y are bit-identical between them):
+ * Two ways to the same bytes (w_hat, scale and Y are bit-identical between them):
  *   GWS_LINEAR_IN_OPERAND   one kernel; the sampling sits in the weight operand load of every
  *                           output tile (no w_hat round trip; each block is resampled once per
  *                           128 rows of X).  Any shape; w_hat/scale optional.
- *   GWS_LINEAR_SAMPLE_ONCE  one persistent kernel: all workgroups sample every block once,
- *                           meet at a device-wide arrival barrier kept in a few device words of
- *                           the library, and run the GEMM on w_hat.  Needs w_hat/scale, M and N
- *                           multiples of 256 and K of 64 (GWS_ERR_SHAPE otherwise).  Two such
- *                           calls must not run concurrently on one GPU; on a stream that is being
- *                           captured into a graph the call records the two kernels below instead.
  *   GWS_LINEAR_TWO_KERNELS  the sampling kernel of gws_sample_fwd, then the plain GEMM on w_hat.
- *                           Needs w_hat/scale (GWS_ERR_NULL otherwise); no state.
+ *                           Needs w_hat/scale (GWS_ERR_NULL otherwise).
  *   GWS_LINEAR_AUTO         two kernels when w_hat/scale are given and M > 128, else in-operand:
  *                           the faster choice as measured on MI355X.
+ * (Mode value 1 belonged to a retired kernel and is rejected with GWS_ERR_FORMAT.)
  * gws_linear_fwd is gws_linear_fwd_mode with GWS_LINEAR_AUTO.                              */
 #define GWS_LINEAR_AUTO 0
-#define GWS_LINEAR_SAMPLE_ONCE 1
 #define GWS_LINEAR_IN_OPERAND 2
 #define GWS_LINEAR_TWO_KERNELS 3
 int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
@@ -187,6 +182,20 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx,
 int gws_linear_fwd_mode(const void* x, int64_t M, int64_t K, int64_t ldx,
                         const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
                         void* y, int64_t ldy, int mode, void* stream);
+
+/* gws_linear_fwd for a caller that wants Y only and many rows of X (Sec. 3.5 keeps sampling and
+ * matmul apart; so does this): w_hat and scale are staged in `workspace` instead of the caller's
+ * buffers (w->w_hat and w->scale are not used), then the plain GEMM runs on the staged w_hat.
+ * Y is bit-identical to gws_linear_fwd's.
+ *   workspace       : device, 256-byte aligned, owned by the caller; contents undefined afterwards;
+ *                     must not overlap x, y or w->w (GWS_ERR_ALIAS)
+ *   workspace_bytes : at least gws_linear_fwd_workspace_bytes(w) (GWS_ERR_SHAPE otherwise)
+ * gws_linear_fwd_workspace_bytes: rows * ld * 2 rounded up to 256, plus 4 bytes per block; 0 for an
+ * empty or invalid descriptor.  Host function, no GPU work.                                      */
+size_t gws_linear_fwd_workspace_bytes(const gws_tensor* w);
+int gws_linear_fwd_ws(const void* x, int64_t M, int64_t K, int64_t ldx,
+                      const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
+                      void* y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Weight gradient of the sampled-weight linear with the reduction of Eq. 4 in the GEMM's
  * epilogue (the linear's backward pass, paper Eq. 2, applied to w_hat):
@@ -225,18 +234,6 @@ int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx,
                               const void* w, int64_t N, int64_t ldw, int w_is_nk,
                               void* y, int64_t ldy,
                               const gws_tensor* next, int fmt, uint64_t step, void* stream);
-
-/* Measurement aid: copies w to w_hat for n tensors with the launch shape, loads and
- * stores of gws_sample_fwd and none of its arithmetic.  Its rate is the ceiling the
- * memory system sets for that access pattern, against which the forward pass is read.
- * Uses fields w, w_hat, rows, cols, ld.                                              */
-int gws_copy_tiles(const gws_tensor* t, int n, void* stream);
-
-/* Step one of Eq. 3 alone: writes max_{b_l}|w| (exact, as fp32) of every 32x32 block into
- * `scale`, for n tensors, with the launch shape and loads of gws_sample_bwd.  It reads
- * each element once and writes 4 bytes per block, so its rate is the ceiling the memory
- * system sets for the backward pass.  Uses fields w, scale, rows, cols, ld.            */
-int gws_block_absmax(const gws_tensor* t, int n, void* stream);
 
 /* The packed noise alone (paper Sec. 3.4: sign-magnitude, 4 bits per element,
  * 8 elements per 32-bit word): out is device u32 [rows x ceil(cols/8)], element

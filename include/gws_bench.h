@@ -1,0 +1,33 @@
+/*
+ * libgws -- measurement aids.  Not part of the method: these calls move the bytes of the
+ * GaussWS forward and backward passes (paper Eq. 3, Eq. 4) with the launch shape, loads and
+ * stores of gws_sample_fwd / gws_sample_bwd and none of their arithmetic, so that a benchmark
+ * can put the rate of the sampling kernels next to the rate the memory system allows for the
+ * same access pattern.  Same conventions as gws.h: device pointers owned by the caller, host
+ * descriptor array read before the call returns, asynchronous on the given stream, gws_status
+ * returned, nothing launched on error.
+ */
+#ifndef GWS_BENCH_H
+#define GWS_BENCH_H
+
+#include "gws.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Copies w to w_hat for n tensors with the launch shape, loads and stores of gws_sample_fwd.
+ * Its rate is the ceiling the memory system sets for that access pattern, against which the
+ * forward pass is read.  Uses fields w, w_hat, rows, cols, ld.                              */
+int gws_copy_tiles(const gws_tensor* t, int n, void* stream);
+
+/* Step one of Eq. 3 alone: writes max_{b_l}|w| (exact, as fp32) of every 32x32 block into
+ * `scale`, for n tensors, with the launch shape and loads of gws_sample_bwd.  It reads
+ * each element once and writes 4 bytes per block, so its rate is the ceiling the memory
+ * system sets for the backward pass.  Uses fields w, scale, rows, cols, ld.                 */
+int gws_block_absmax(const gws_tensor* t, int n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GWS_BENCH_H */

@@ -120,10 +120,11 @@ static void group_words(int64_t i, int64_t cg, uint64_t seed, uint64_t step,
   gwso_philox4x32(ctr, key, 10, x);
 }
 
-/* Which nibble of each Philox word belongs to element k (= j & 7) of a group:
+/* Which nibble of each Philox word belongs to element k (= j & 7) of a group.
+ * Sec. 3.4 fixes 4 bits per element and 8 elements per 32-bit word but not which
+ * bits go to which element, so the assignment is a free choice; it is frozen as:
  * each 32-bit word is seen as two 16-bit halves, the low half serving the even
- * elements and the high half the odd ones (the way two BF16 values share a
- * 32-bit register); pair k>>1 takes nibble k>>1 of its half.                 */
+ * elements and the high half the odd ones; pair k>>1 takes nibble k>>1 of its half. */
 int gwso_element_nibble(int k) { return (k >> 1) + 4 * (k & 1); }
 
 static int element_code(const uint32_t x[4], int k) {

@@ -15,10 +15,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
-LINEAR_AUTO, LINEAR_SAMPLE_ONCE, LINEAR_IN_OPERAND, LINEAR_TWO_KERNELS = 0, 1, 2, 3
+LINEAR_AUTO, LINEAR_IN_OPERAND, LINEAR_TWO_KERNELS = 0, 2, 3
 
-EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode", "gws_linear_bwd_w",
-           "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_copy_tiles", "gws_block_absmax", "gws_noise_packed", "gws_derive_seed", "gws_status_string", "gws_version")
+# include/gws.h (the method) and include/gws_bench.h (measurement aids)
+EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode",
+           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
+           "gws_derive_seed", "gws_status_string", "gws_version")
+BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax")
 
 
 class GwsError(RuntimeError):
@@ -113,6 +116,10 @@ def load_library() -> ctypes.CDLL:
     L.gws_linear_fwd.restype = ci
     L.gws_linear_fwd_mode.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, ci, vp]
     L.gws_linear_fwd_mode.restype = ci
+    L.gws_linear_fwd_ws.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp, ctypes.c_size_t, vp]
+    L.gws_linear_fwd_ws.restype = ci
+    L.gws_linear_fwd_workspace_bytes.argtypes = [tp]
+    L.gws_linear_fwd_workspace_bytes.restype = ctypes.c_size_t
     L.gws_gemm_bf16_sample_next.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, tp, ci, u64, vp]
     L.gws_gemm_bf16_sample_next.restype = ci
     L.gws_copy_tiles.argtypes = [tp, ci, vp]
@@ -280,7 +287,7 @@ def gws_sample_fwd_mx(t: Sequence[TensorDesc], o: Sequence[MxOut], fmt: int, ste
 
 
 def gws_linear_fwd(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:
-    """Y = X * w_hat, the weight sampled as in ``gws_sample_fwd``; the library picks the fastest of its three ways."""
+    """Y = X * w_hat, the weight sampled as in ``gws_sample_fwd``; the library picks the faster of its two ways."""
     L = load_library()
     M, K = int(x.shape[0]), int(x.shape[1])
     _check(L.gws_linear_fwd(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt),
@@ -293,6 +300,20 @@ def gws_linear_fwd_mode(x, w: TensorDesc, y, fmt: int, step: int, mode: int, w_i
     M, K = int(x.shape[0]), int(x.shape[1])
     _check(L.gws_linear_fwd_mode(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt),
                                  int(step), _p(y), int(y.stride(0)), int(mode), _stream(stream)), "gws_linear_fwd_mode")
+
+
+def gws_linear_fwd_workspace_bytes(w: TensorDesc) -> int:
+    """Bytes of device workspace ``gws_linear_fwd_ws`` needs for this weight."""
+    return int(load_library().gws_linear_fwd_workspace_bytes(_marshal([w])))
+
+
+def gws_linear_fwd_ws(x, w: TensorDesc, y, fmt: int, step: int, workspace, w_is_nk: bool = False, stream=None) -> None:
+    """``gws_linear_fwd`` with w_hat and scale staged in ``workspace`` (a uint8 device tensor) instead of the caller's buffers."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    _check(L.gws_linear_fwd_ws(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt), int(step),
+                               _p(y), int(y.stride(0)), _p(workspace), int(workspace.numel() * workspace.element_size()),
+                               _stream(stream)), "gws_linear_fwd_ws")
 
 
 def gws_linear_bwd_w(x, dy, w: TensorDesc, step: int, w_is_nk: bool = False, stream=None) -> None:

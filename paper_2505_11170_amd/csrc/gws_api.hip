@@ -2,6 +2,7 @@
 // the meaning of every argument are in include/gws.h.
 #include <string.h>
 
+#include "gws_bench.h"
 #include "gws_launch.h"
 
 namespace {
@@ -170,6 +171,57 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   return flush();
 }
 
+// Argument rules shared by the forms of the sampled-weight linear (w is not NULL).  Returns GWS_OK
+// also for an empty product (M == 0 or N == 0), which the caller skips.
+int check_linear(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk, const void* y,
+                 int64_t ldy) {
+  int rc = check_shape(*w);
+  if (rc != GWS_OK) return rc;
+  const int64_t Kw = w_is_nk ? w->cols : w->rows, N = w_is_nk ? w->rows : w->cols;
+  if (M < 0 || K < 0 || K != Kw || M >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (M == 0 || N == 0) return GWS_OK;
+  if ((K & 31) != 0 || (N & 31) != 0 || K == 0) return GWS_ERR_SHAPE;
+  if (ldx < K || ldy < N || (ldx & 7) != 0 || (ldy & 7) != 0 || ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
+  if (!x || !y || !w->w || !w->bt) return GWS_ERR_NULL;
+  if (!aligned(x, 16) || !aligned(y, 16) || !aligned(w->w, 16) || !aligned(w->bt, 4)) return GWS_ERR_ALIGN;
+  return GWS_OK;
+}
+
+GemmArgs linear_args(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk, uint64_t step,
+                     void* y, int64_t ldy) {
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.x = (const uint16_t*)x; g.w = (const uint16_t*)w->w; g.y = (uint16_t*)y;
+  g.M = (uint32_t)M; g.N = (uint32_t)(w_is_nk ? w->rows : w->cols); g.K = (uint32_t)K;
+  g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)w->ld; g.ldy = (uint32_t)ldy;
+  g.bt = w->bt;
+  g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
+  g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
+  g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
+  return g;
+}
+
+// Bytes of the staged w_hat of a weight, rounded up so that the block scales behind it stay aligned.
+inline size_t staged_bytes(const gws_tensor& w) { return (((size_t)w.rows * (size_t)w.ld * 2) + 255) & ~(size_t)255; }
+
+// The sampled-weight linear with w_hat and scale staged in `staging` (device, 256-byte aligned, at least
+// gws_linear_fwd_workspace_bytes(w)): the sampling kernel writes them there, the plain GEMM reads w_hat.
+// Arguments already checked.
+int linear_staged(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk, int fmt,
+                  uint64_t step, void* y, int64_t ldy, void* staging, hipStream_t stream) {
+  gws_tensor t = *w;
+  t.w_hat = staging;
+  t.scale = (float*)((char*)staging + staged_bytes(*w));
+  const size_t w_bytes = (size_t)w->rows * w->ld * 2, need = staged_bytes(*w) + (size_t)((w->rows + 31) / 32) * ((w->cols + 31) / 32) * 4;
+  if (overlap2(staging, need, w->w, w_bytes) || overlap2(staging, need, x, (size_t)M * ldx * 2) ||
+      overlap2(staging, need, y, (size_t)M * ldy * 2)) return GWS_ERR_ALIAS;
+  int rc = run_batched(&t, 1, nullptr, nullptr, true, fmt, step, stream, /*keep=*/true);
+  if (rc != GWS_OK) return rc;
+  GemmArgs g = linear_args(x, M, K, ldx, w, w_is_nk, step, y, ldy);
+  g.w = (const uint16_t*)staging;
+  return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -282,51 +334,45 @@ int gws_linear_fwd_mode(const void* x, int64_t M, int64_t K, int64_t ldx, const 
                         int fmt, uint64_t step, void* y, int64_t ldy, int mode, void* stream) {
   if (!w) return GWS_ERR_NULL;
   if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
-  if (mode < GWS_LINEAR_AUTO || mode > GWS_LINEAR_TWO_KERNELS) return GWS_ERR_FORMAT;
-  int rc = check_shape(*w);
-  if (rc != GWS_OK) return rc;
-  const int64_t Kw = w_is_nk ? w->cols : w->rows, N = w_is_nk ? w->rows : w->cols;
-  if (M < 0 || K < 0 || K != Kw || M >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
-  if (M == 0 || N == 0) return GWS_OK;
-  if ((K & 31) != 0 || (N & 31) != 0 || K == 0) return GWS_ERR_SHAPE;
-  if (ldx < K || ldy < N || (ldx & 7) != 0 || (ldy & 7) != 0 || ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
-  if (!x || !y || !w->w || !w->bt) return GWS_ERR_NULL;
+  if (mode != GWS_LINEAR_AUTO && mode != GWS_LINEAR_IN_OPERAND && mode != GWS_LINEAR_TWO_KERNELS) return GWS_ERR_FORMAT;
+  int rc = check_linear(x, M, K, ldx, w, w_is_nk, y, ldy);
+  if (rc != GWS_OK || M == 0 || (w_is_nk ? w->rows : w->cols) == 0) return rc;
   if ((w->w_hat == nullptr) != (w->scale == nullptr)) return GWS_ERR_NULL;
-  if (!aligned(x, 16) || !aligned(y, 16) || !aligned(w->w, 16) || !aligned(w->w_hat, 16) ||
-      !aligned(w->bt, 4) || !aligned(w->scale, 4)) return GWS_ERR_ALIGN;
+  if (!aligned(w->w_hat, 16) || !aligned(w->scale, 4)) return GWS_ERR_ALIGN;
   if (w->w_hat && overlap(w->w, w->w_hat, (size_t)w->rows * w->ld * 2)) return GWS_ERR_ALIAS;
-  GemmArgs g;
-  memset(&g, 0, sizeof g);
-  g.x = (const uint16_t*)x; g.w = (const uint16_t*)w->w; g.y = (uint16_t*)y;
-  g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
-  g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)w->ld; g.ldy = (uint32_t)ldy;
-  g.bt = w->bt; g.scale = w->scale; g.w_hat = (uint16_t*)w->w_hat;
-  g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
-  g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
-  g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
+  GemmArgs g = linear_args(x, M, K, ldx, w, w_is_nk, step, y, ldy);
+  g.scale = w->scale; g.w_hat = (uint16_t*)w->w_hat;
   if (mode == GWS_LINEAR_AUTO) {
     // Measured on MI355X: once more than one row of output tiles shares the weight, sampling it
-    // once with the streaming kernel and running the plain GEMM on w_hat beats both fused kernels.
+    // once with the streaming kernel and running the plain GEMM on w_hat beats the fused kernel.
     mode = (w->w_hat && M > 128) ? GWS_LINEAR_TWO_KERNELS : GWS_LINEAR_IN_OPERAND;
   }
-  if (mode == GWS_LINEAR_TWO_KERNELS && !w->w_hat) return GWS_ERR_NULL;
-  if (mode == GWS_LINEAR_SAMPLE_ONCE) {
-    if (!linear256_fused_applicable(g)) return GWS_ERR_SHAPE;
-    // The sample-once kernel tells its calls apart by an epoch passed as a kernel argument; a
-    // captured launch would replay one epoch against the synchronisation words it left behind.
-    // Under stream capture the same bytes come from the two stateless launches instead.
-    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-    if (stream != nullptr && hipStreamIsCapturing((hipStream_t)stream, &capture) != hipSuccess) return GWS_ERR_LAUNCH;
-    if (capture != hipStreamCaptureStatusNone) mode = GWS_LINEAR_TWO_KERNELS;
-  }
   if (mode == GWS_LINEAR_TWO_KERNELS) {
+    if (!w->w_hat) return GWS_ERR_NULL;
     rc = run_batched(w, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, /*keep=*/true);
     if (rc != GWS_OK) return rc;
     g.w = g.w_hat;
     return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
   }
-  return launch_gemm(g, w_is_nk, mode == GWS_LINEAR_SAMPLE_ONCE ? kFusedSampleOnce : kFusedInOperand, fmt,
-                     (hipStream_t)stream);
+  return launch_gemm(g, w_is_nk, kFusedInOperand, fmt, (hipStream_t)stream);
+}
+
+size_t gws_linear_fwd_workspace_bytes(const gws_tensor* w) {
+  if (!w || check_shape(*w) != GWS_OK || w->rows == 0 || w->cols == 0) return 0;
+  return staged_bytes(*w) + (size_t)((w->rows + 31) / 32) * (size_t)((w->cols + 31) / 32) * sizeof(float);
+}
+
+int gws_linear_fwd_ws(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
+                      int fmt, uint64_t step, void* y, int64_t ldy, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  if (!w) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  int rc = check_linear(x, M, K, ldx, w, w_is_nk, y, ldy);
+  if (rc != GWS_OK || M == 0 || (w_is_nk ? w->rows : w->cols) == 0) return rc;
+  if (!workspace) return GWS_ERR_NULL;
+  if (!aligned(workspace, 256)) return GWS_ERR_ALIGN;
+  if (workspace_bytes < gws_linear_fwd_workspace_bytes(w)) return GWS_ERR_SHAPE;
+  return linear_staged(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, workspace, (hipStream_t)stream);
 }
 
 int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,

@@ -75,9 +75,8 @@ struct GemmArgs {
   uint32_t row0, cg0, seed_lo, seed_hi, step_lo, step_hi;
   float* dbt;          // weight-gradient GEMM only: dL/db_t per block (with scale as input)
 };
-// fused: 0 = plain GEMM on g.w; kFusedSampleOnce = cooperative sampling prologue + GEMM on w_hat (needs
-// linear256_fused_applicable); kFusedInOperand = sampling in the weight operand load of every tile
-constexpr int kFusedSampleOnce = 1, kFusedInOperand = 2;
+// fused: 0 = plain GEMM on g.w; kFusedInOperand = sampling in the weight operand load of every tile
+constexpr int kFusedInOperand = 2;
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
@@ -86,8 +85,6 @@ int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
 int launch_gemm256_ride(const GemmArgs& g, int w_is_nk, const TileDesc& d, int fmt, uint64_t step, uint32_t extra,
                         hipStream_t stream);
 int compute_units();   // of the current device; 0 if the query fails
-bool linear256_fused_applicable(const GemmArgs& g);
-int launch_linear256_fused(const GemmArgs& g, int w_is_nk, int fmt, hipStream_t stream);
 // Weight-gradient GEMM (gws_gemm256_tn.hip): y[M x N] = x^T * w with x [K x M], w [K x N]
 // row-major (K = the contraction length); with_dbt adds Eq. 4's block reduction on y.
 bool gemm256_tn_applicable(const GemmArgs& g);

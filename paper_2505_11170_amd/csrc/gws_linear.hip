@@ -187,10 +187,6 @@ int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t 
   if (tiles >= 0x7FFFFFFFull) return GWS_ERR_SHAPE;
   const dim3 grid((uint32_t)tiles);
   if (!fused && gemm256_applicable(g)) return launch_gemm256(g, w_is_nk, stream);
-  if (fused == kFusedSampleOnce) {
-    if (!linear256_fused_applicable(g)) return GWS_ERR_SHAPE;
-    return launch_linear256_fused(g, w_is_nk, fmt, stream);
-  }
   if (!fused) return launch_layout<false, 0>(g, w_is_nk, grid, stream);
   switch (fmt) {
     case GWS_FMT_BF16: return launch_layout<true, 0>(g, w_is_nk, grid, stream);

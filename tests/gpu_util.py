@@ -8,6 +8,9 @@ import paper_2505_11170_amd as gws
 from paper_2505_11170_amd import synth
 
 DEV = "cuda:0"
+# Largest share of blocks for which the additive rounding floor of assert_dbt_close, not its 1e-5 relative
+# term, may be what accepts the GPU's dL/db_t (blocks whose 1024 signed terms cancel almost completely).
+CANCELLATION_SHARE = 0.10
 
 
 def ensure_built():

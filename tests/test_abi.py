@@ -22,8 +22,8 @@ def lib():
     return binding.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "gws.h")).read()
+def declared_symbols(header="gws.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(gws_[a-z0-9_]+)\s*\(", text)))
 
@@ -35,6 +35,11 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, n), n
     assert set(names) == set(binding.EXPORTS)
     assert lib.gws_version() >= 1
+    # the method's header lists no measurement aid; those live in their own header
+    bench = declared_symbols("gws_bench.h")
+    assert set(bench) == set(binding.BENCH_EXPORTS) and not set(bench) & set(names)
+    for n in bench:
+        assert hasattr(lib, n), n
 
 
 def test_derive_seed_matches_oracle(lib):
@@ -85,8 +90,19 @@ def test_argument_validation_launches_nothing(lib):
     assert lib.gws_linear_fwd(fake, 8, 64, 64, wdesc, 0, 9, 0, fake, 64, None) == FORMAT
     assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, 4, None) == FORMAT    # no such mode
     assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, -1, None) == FORMAT
-    assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, 1, None) == SHAPE     # sample-once needs 256-tiles
+    assert lib.gws_linear_fwd_mode(fake, 8, 64, 64, wdesc, 0, 1, 0, fake, 64, 1, None) == FORMAT    # a retired mode value
     assert lib.gws_linear_fwd_mode(fake, 0, 64, 64, wdesc, 0, 1, 0, fake, 64, 3, None) == OK        # empty
+    # linear with w_hat staged in a workspace: the workspace is checked like any buffer
+    need = lib.gws_linear_fwd_workspace_bytes(wdesc)
+    assert need == 64 * 64 * 2 + 4 * 4 and lib.gws_linear_fwd_workspace_bytes(None) == 0
+    ws = fake + 0x900000
+    lin = (fake + 0x300000, 8, 64, 64, wdesc, 0, 1, 0, fake + 0x500000, 64)
+    assert lib.gws_linear_fwd_ws(*lin, None, need, None) == NULL
+    assert lib.gws_linear_fwd_ws(*lin, ws + 16, need, None) == ALIGN
+    assert lib.gws_linear_fwd_ws(*lin, ws, need - 1, None) == SHAPE
+    assert lib.gws_linear_fwd_ws(*lin, fake, need, None) == ALIAS                                  # workspace on w
+    assert lib.gws_linear_fwd_ws(*lin, fake + 0x500000, need, None) == ALIAS                       # workspace on y
+    assert lib.gws_linear_fwd_ws(fake, 0, 64, 64, wdesc, 0, 1, 0, fake, 64, None, 0, None) == OK   # empty
     assert lib.gws_gemm_bf16(fake, 8, 48, 48, fake, 64, 64, 0, fake, 64, None) == SHAPE      # K % 32
     assert lib.gws_gemm_bf16(None, 8, 64, 64, fake, 64, 64, 0, fake, 64, None) == NULL
     assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty

@@ -15,7 +15,7 @@ import torch
 import oracle
 import paper_2505_11170_amd as gws
 from paper_2505_11170_amd import synth
-from gpu_util import DEV, assert_dbt_close, ensure_built
+from gpu_util import CANCELLATION_SHARE, DEV, assert_dbt_close, ensure_built
 
 pytestmark = pytest.mark.gpu
 
@@ -60,6 +60,9 @@ def test_config3_llama_1b_every_element_fwd_bwd():
         needed += assert_dbt_close(d.dbt.cpu().numpy(), ref_dbt, asum, shapes[i])
         d.w_hat = d.dw = None   # free as we go
     print(f"config 3: blocks needing the cancellation term of the db_t tolerance: {needed} of 946176")
+    # the benchmark spec's tolerance is the relative term; the additive floor may only be what decides for the few blocks
+    # whose +- terms cancel to below 1e-5 of their absolute sum
+    assert needed <= CANCELLATION_SHARE * 946176
 
 
 @pytest.mark.parametrize("fmt_name", list(FMTS))
@@ -84,13 +87,17 @@ def test_config4_precision_sweep(fmt_name):
                 assert (synth.bits(d.dw) == ref_dw).all()
                 assert_dbt_close(d.dbt.cpu().numpy(), ref_dbt, asum, (sh, bt))
         del descs
-    # (b) the full model in one descriptor list, sampled blocks (heterogeneous and 6-bit cells)
-    for bt in (None, 6.0):
-        descs = device_set(shapes, bt=bt, with_grad=False)
-        pk = gws.pack(descs)
+    # (b) the full model in one descriptor list, sampled blocks, in every one of the seven precision settings
+    # (the weights are the same in all of them: only the b_t tables change between the launches)
+    descs = device_set(shapes, bt=None, with_grad=False)
+    het = [d.bt.clone() for d in descs]
+    pk = gws.pack(descs)
+    for bt in PRECISIONS:
+        for d, h in zip(descs, het):
+            d.bt.copy_(h) if bt is None else d.bt.fill_(bt)
         gws.gws_sample_fwd(pk, fmt, 2)
         torch.cuda.synchronize()
-        for _ in range(96):
+        for _ in range(64):
             ti = int(rng.integers(0, len(descs)))
             d = descs[ti]
             bi, bj = int(rng.integers(0, d.rows // 32)), int(rng.integers(0, d.cols // 32))
@@ -100,8 +107,8 @@ def test_config4_precision_sweep(fmt_name):
             got = synth.bits(d.w_hat[bi * 32:bi * 32 + 32, bj * 32:bj * 32 + 32].contiguous())
             assert (got == ref_q).all(), (ti, bi, bj, bt)
             assert d.scale[bi, bj].item() == ref_s[0, 0]
-        del descs, pk
-        torch.cuda.empty_cache()
+    del descs, pk, het
+    torch.cuda.empty_cache()
 
 
 def test_one_tensor_beyond_4_gib_matches_its_shards_and_the_oracle():

@@ -27,8 +27,7 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
         descs.append(gws.TensorDesc(rows=r, cols=c, seed=gws.gws_derive_seed(9, i), w=t["w"], w_hat=w_hat, bt=t["bt"],
                                     scale=scale, g=t["g"], dw=dw, dbt=dbt, ld=t["w"].stride(0)))
         outs += [w_hat, scale, dbt, dw]
-    # a linear whose shape admits the sample-once kernel: asked for explicitly, it runs that kernel eagerly
-    # and records the two stateless kernels under capture
+    # a sampled-weight linear on the large tile (sampling kernel + GEMM), and the same with w_hat staged in a workspace
     M, K, N = 512, 256, 512
     x = synth.make_activation(710, M, K, device=DEV)
     tl = synth.make_tensor(711, K, N, bt=6.0, device=DEV, with_grad=False)
@@ -36,6 +35,10 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
     y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
     dlin = gws.TensorDesc(rows=K, cols=N, seed=5, w=tl["w"], w_hat=lw_hat, bt=tl["bt"], scale=lscale)
     outs += [lw_hat, lscale, y]
+    dbare = gws.TensorDesc(rows=K, cols=N, seed=5, w=tl["w"], bt=tl["bt"])
+    ws = torch.zeros(gws.gws_linear_fwd_workspace_bytes(dbare), dtype=torch.uint8, device=DEV)
+    y3 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    outs += [ws, y3]
     # the plain GEMM with the sampling of another weight riding in its launch
     y2 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
     tn = synth.make_tensor(712, 768, 768, device=DEV, with_grad=False)
@@ -46,7 +49,8 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
     def run():
         gws.gws_sample_fwd(descs, fmt, step)
         gws.gws_sample_bwd(descs, step)
-        gws.gws_linear_fwd_mode(x, dlin, y, fmt, step, gws.LINEAR_SAMPLE_ONCE)
+        gws.gws_linear_fwd(x, dlin, y, fmt, step)
+        gws.gws_linear_fwd_ws(x, dbare, y3, fmt, step, ws)
         gws.gws_gemm_bf16_sample_next(x, tl["w"], y2, dnext, fmt, step)
 
     run()                                      # eager reference (also the usual warm-up before a capture)

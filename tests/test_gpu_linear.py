@@ -1,6 +1,6 @@
-"""GPU parity of gws_linear_fwd / gws_linear_fwd_mode (the sampled-weight linear in its three
-forms: sampling in the weight operand load, cooperative sample-once kernel, sampling kernel +
-plain GEMM) and of the plain twin gws_gemm_bf16, through the C ABI.
+"""GPU parity of gws_linear_fwd / gws_linear_fwd_mode / gws_linear_fwd_ws (the sampled-weight
+linear in its forms: sampling in the weight operand load, sampling kernel + plain GEMM with w_hat
+in the caller's buffer or staged in a workspace) and of the plain twin gws_gemm_bf16, through the C ABI.
 
  - w_hat / scale written by the call: bit-exact against the oracle forward.
  - Y against the oracle's fp64 GEMM on the oracle's w_hat: |y - ref| <= 2^-8 |ref| +
@@ -80,6 +80,16 @@ def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, l
     gws.gws_linear_fwd(x, gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, bt=btd), y3, fmt, step, w_is_nk=w_is_nk)
     torch.cuda.synchronize()
     assert (synth.bits(y3) == y_bits).all()
+    # 5. ... and with w_hat staged in a caller's workspace (poisoned first, oversized: the tail stays as it was)
+    bare = gws.TensorDesc(rows=wr, cols=wc, seed=seed, w=w, bt=btd)
+    need = gws.gws_linear_fwd_workspace_bytes(bare)
+    assert need == ((wr * wc * 2 + 255) // 256) * 256 + 4 * nbr * nbc
+    ws = torch.full((need + 512,), 0xA5, dtype=torch.uint8, device=DEV)
+    y4 = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_linear_fwd_ws(x, bare, y4, fmt, step, ws, w_is_nk=w_is_nk)
+    torch.cuda.synchronize()
+    assert (synth.bits(y4) == y_bits).all()
+    assert (ws[need:] == 0xA5).all()
 
 
 @pytest.mark.parametrize("w_is_nk", [False, True])
@@ -134,22 +144,26 @@ def test_plain_gemm_large_tile_path(w_is_nk):
 
 @pytest.mark.parametrize("w_is_nk", [False, True])
 @pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
-def test_linear_sample_once_path(w_is_nk, fmt):
-    # M, N multiples of 256, K of 64 and w_hat requested: cooperative sampling prologue + GEMM on w_hat
-    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2, mode=gws.LINEAR_SAMPLE_ONCE)
-    run_case(256, 64, 256, w_is_nk, fmt, bt=3.0, seed_id=8, mode=gws.LINEAR_SAMPLE_ONCE)
-    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2)        # automatic choice: two kernels, 256-tile GEMM
+def test_linear_on_the_large_tile(w_is_nk, fmt):
+    # M, N multiples of 256, K of 64 and w_hat requested: sampling kernel + the 256-tile GEMM on w_hat
+    run_case(512, 128, 768, w_is_nk, fmt, seed_id=7, step=2)
+    run_case(256, 64, 256, w_is_nk, fmt, bt=3.0, seed_id=8)
 
 
-def test_linear_sample_once_repeated_calls_reuse_the_sync_words():
-    for step in range(4):
-        run_case(512, 192, 512, False, gws.FMT_FP8_E4M3, seed_id=9, step=step, mode=gws.LINEAR_SAMPLE_ONCE)
+def tile_rows(M, rng, tile=256, sub=32):
+    """One row in every `tile`-row output tile, at a different 32-row MFMA sub-tile and lane row each time,
+    plus the first and last row: every M-tile and, over the tiles, every wavefront quadrant is hit."""
+    rows = {0, M - 1}
+    for t in range(M // tile):
+        rows.add(t * tile + sub * (t % (tile // sub)) + int(rng.integers(0, sub)))
+    return np.array(sorted(rows))
 
 
-def test_config5_fused_linear_8192x2048x5632_sampled_rows():
+def test_config5_fused_linear_8192x2048x5632_a_row_in_every_tile():
     M, K, N = 8192, 2048, 5632
-    rows_sel = np.array([0, 1, 31, 127, 128, 4095, 4096, 8000, 8191])
-    for mode in (None, gws.LINEAR_SAMPLE_ONCE, gws.LINEAR_IN_OPERAND):
+    rows_sel = tile_rows(M, np.random.default_rng(5))
+    assert len(rows_sel) >= 32 and len(set(rows_sel // 256)) == 32
+    for mode in (None, gws.LINEAR_IN_OPERAND):
         run_case(M, K, N, False, gws.FMT_FP8_E4M3, bt=6.0, seed_id=5, rows_sel=rows_sel, mode=mode)
 
 
@@ -161,8 +175,8 @@ def test_linear_mode_errors():
     full = gws.TensorDesc(rows=96, cols=160, seed=1, w=w, bt=bt, w_hat=torch.zeros_like(w), scale=torch.zeros(3, 5, device=DEV))
     bare = gws.TensorDesc(rows=96, cols=160, seed=1, w=w, bt=bt)
     with pytest.raises(gws.GwsError) as e:
-        gws.gws_linear_fwd_mode(x, full, y, gws.FMT_FP8_E4M3, 0, gws.LINEAR_SAMPLE_ONCE)    # not a 256-tile shape
-    assert e.value.status == 2
+        gws.gws_linear_fwd_mode(x, full, y, gws.FMT_FP8_E4M3, 0, 1)                         # a retired mode value
+    assert e.value.status == 4
     with pytest.raises(gws.GwsError) as e:
         gws.gws_linear_fwd_mode(x, bare, y, gws.FMT_FP8_E4M3, 0, gws.LINEAR_TWO_KERNELS)    # nowhere to put w_hat
     assert e.value.status == 1
@@ -241,6 +255,6 @@ def test_gemm_next_without_idle_compute_units_and_without_next():
 
 
 def test_config5_gemm_with_the_next_weight_sampled_alongside():
-    rows_sel = np.array([0, 1, 127, 128, 4095, 4096, 8191])
+    rows_sel = tile_rows(8192, np.random.default_rng(6))
     run_next_case(8192, 2048, 5632, False, 2048, 5632, gws.FMT_FP8_E4M3, 6, rows_sel=rows_sel)   # too much to ride: two launches
     run_next_case(8192, 2048, 5632, False, 2048, 2048, gws.FMT_FP8_E4M3, 7, rows_sel=rows_sel)   # rides beside the last round of tiles

@@ -89,7 +89,11 @@ MUTANTS = [
     ("linear: weight layout flag inverted", "w_is_nk ? q[n * ldq + k] : q[k * ldq + n]", "w_is_nk ? q[k * ldq + n] : q[n * ldq + k]",
      [smp.test_linear_vs_numpy_fp64_matmul]),
     ("linear: rounding of Y truncates", "if (rem > half || (rem == half && (keep & 1))) keep += 1;\n  int ef", "int ef",
-     [smp.test_linear_vs_numpy_fp64_matmul]),
+     [smp.test_linear_bf16_output_rounds_once_to_nearest_even]),
+    ("linear: ties of Y rounded away from zero", "if (rem > half || (rem == half && (keep & 1))) keep += 1;\n  int ef",
+     "if (rem >= half) keep += 1;\n  int ef", [smp.test_linear_bf16_output_rounds_once_to_nearest_even]),
+    ("linear: subnormal Y flushed to zero", "if (E < -126) drop += (-126 - E);", "if (E < -126) return (uint16_t)(sign << 15);",
+     [smp.test_linear_bf16_output_rounds_once_to_nearest_even]),
     ("Eq. 11: offset is b_init instead of b_target", "bt[k] = b_target + prod;", "bt[k] = b_init + prod;",
      [bw.test_eq11_end_points_and_midpoint]),
     ("Eq. 11: slope sign", "float delta = b_init - b_target;\n  for (int64_t k = 0; k < n; ++k) {\n    float prod = bi[k] * delta;\n    bt[k]",

@@ -238,16 +238,47 @@ def test_bt9_tie_erases_noise_on_bf16():
     assert bf16_val(q)[i, j] == 1.0
 
 
-def test_table_c1_formulas():
-    # Sec. 3.3 with tau = 0: exponent bits ceil(log2(b_t+1)) for w, ceil(log2(b_t+3)) for
-    # w_hat, mantissa b_t - 2; must reproduce every printed row of Table C.1.
+def table_c1_rows():
     path = os.path.join(os.path.dirname(__file__), "golden", "table_c1.txt")
     rows = [list(map(int, l.split())) for l in open(path) if l.strip() and not l.startswith("#")]
     assert len(rows) == 11
-    for bt, ew, e, m in rows:
-        assert ew == int(np.ceil(np.log2(bt + 1)))
-        assert e == int(np.ceil(np.log2(bt + 3)))
-        assert m == bt - 2
+    return rows
+
+
+@pytest.mark.parametrize("row", table_c1_rows(), ids=lambda r: f"bt{r[0]}")
+def test_table_c1_exponent_ranges_hold_on_the_oracle_output(row):
+    # Appendix C, Table C.1 / Prop. 3 (tau = 0): weights that occupy the b_t - 1 binades from the block maximum's
+    # downward need `ew` exponent bits; their sampled counterparts occupy at most b_t + 1 normal binades, from the
+    # headroom binade above the maximum's down to the binade of the smallest PQN, which is what `e` exponent bits
+    # (normal ranges + a subnormal range + a NaN/Inf range) provide.  Checked on what gwso_sample_fwd returns.
+    bt, ew, e, m = row
+    # the printed row follows the closed forms of Sec. 3.3
+    assert ew == int(np.ceil(np.log2(bt + 1))) and e == int(np.ceil(np.log2(bt + 3))) and m == bt - 2
+    if bt > 9:
+        return                                             # beyond what the BF16 operator of Sec. 3.3 supports
+    rng = np.random.default_rng(bt)
+    rows = cols = 64
+    n_bin = bt - 1                                         # binades of w: the maximum's and b_t - 2 below it
+    assert n_bin + 2 <= 2 ** ew                            # ... which is what the table's `ew` bits hold
+    expo = -rng.integers(0, n_bin, size=(rows, cols))
+    wv = np.ldexp(1.0 + rng.integers(0, 128, size=(rows, cols)) / 128.0, expo) * rng.choice([-1.0, 1.0], size=(rows, cols))
+    for bi in range(2):
+        for bj in range(2):
+            wv[bi * 32 + 1, bj * 32 + 2] = 1.9921875       # block maximum: the top of [1, 2), so Ea = 0
+    w = to_bits(wv)
+    fmt = oracle.FMT_FP6_E3M2 if bt <= 4 else oracle.FMT_FP8_E4M3 if bt == 5 else oracle.FMT_BF16   # the table's datatype column
+    q, scale = oracle.sample_fwd(w, np.full((2, 2), float(bt), np.float32), fmt, 11, bt)
+    r, _ = oracle.noise(rows, cols, 11, bt)
+    qv = np.abs(bf16_val(q))
+    assert (r != 0).sum() > 500 and (qv != np.abs(bf16_val(w))).any()
+    assert qv.max() < 4.0                                  # never past the headroom binade [2, 4) (Eq. in Prop. 3's proof)
+    assert (qv[r == 0] != 0).all()                         # where R = 0 no weight of this range underflows in the datatype
+    nz = qv[qv > 0]
+    lowest_pqn_binade = np.floor(np.log2(scale.min()))     # = floor(1 - b_t + log2 max|w|)
+    normal = nz[np.log2(nz) >= lowest_pqn_binade]
+    binades = np.unique(np.floor(np.log2(normal)))
+    assert binades.max() <= 1 and binades.min() >= lowest_pqn_binade
+    assert len(binades) <= bt + 1 <= 2 ** e - 2            # b_t + 1 normal ranges fit e exponent bits
 
 
 def test_all_zero_block_and_negative_zero():
@@ -366,3 +397,28 @@ def test_linear_vs_numpy_fp64_matmul():
     qt = np.ascontiguousarray(q.T)
     y64b, _, _ = oracle.linear_fwd(x, qt, w_is_nk=True, rows_sel=[5, 0, 36])
     assert np.allclose(y64b, ref[[5, 0, 36]], rtol=1e-12, atol=1e-15)
+
+
+def test_linear_bf16_output_rounds_once_to_nearest_even():
+    # the BF16 form of Y (one RNE of the fp64 sum): (a) sums that are exact in any order (small integers) must equal
+    # torch's conversion bit for bit; (b) constructed ties and near-ties, subnormal results included
+    rng = np.random.default_rng(3)
+    xi = rng.integers(-8, 9, size=(24, 40)).astype(np.float64)
+    qi = rng.integers(-8, 9, size=(40, 56)).astype(np.float64)
+    _, _, y16 = oracle.linear_fwd(to_bits(xi), to_bits(qi))
+    want = torch.from_numpy((xi @ qi).astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (y16 == want).all()
+    def y_of(xs, qs):
+        _, _, y = oracle.linear_fwd(to_bits(np.array([xs])), to_bits(np.array(qs).reshape(-1, 1)))
+        return int(y[0, 0])
+    assert y_of([1.0, 1.0], [1.0, 2.0 ** -8]) == 0x3F80                        # 1 + 2^-8: tie, even neighbour is 1.0
+    assert y_of([1.0, 1.0], [1.0078125, 2.0 ** -8]) == 0x3F82                  # 1.01171875: tie, even neighbour is 1.015625
+    assert y_of([1.0, 1.0, 1.0], [1.0, 2.0 ** -8, 2.0 ** -16]) == 0x3F81       # just above the tie: up
+    assert y_of([1.0, 1.0, -1.0], [1.0078125, 2.0 ** -8, 2.0 ** -16]) == 0x3F81   # just below the tie: down
+    assert y_of([1.0, 1.0], [-1.0, -2.0 ** -8]) == 0xBF80                      # sign-symmetric
+    assert y_of([1.0, 1.0], [255.0, 1.0]) == 0x4380 and y_of([1.0, 1.0], [254.0, 1.0]) == 0x437F   # carry into the next binade
+    tiny = 2.0 ** -133                                                         # the smallest BF16 subnormal
+    assert y_of([0.5, 0.0], [tiny, 0.0]) == 0x0000                             # half of it: tie between 0 and 1 ulp -> 0
+    assert y_of([0.5, 0.5], [tiny, 2 * tiny]) == 0x0002                        # 1.5 ulp: tie -> 2 ulp
+    assert y_of([0.75, 0.0], [tiny, 0.0]) == 0x0001
+    assert y_of([1.0, 1.0], [127 * tiny, 0.5 * 2 * tiny]) == 0x0080            # subnormals carrying into the lowest normal
