@@ -20,6 +20,7 @@ _SRC = os.path.join(_HERE, "gws_oracle.c")
 _LIB = os.path.join(_HERE, "libgws_oracle.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
+BASIS_BITS, BASIS_UNIFORM, BASIS_BOX_MULLER = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -70,6 +71,20 @@ def configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.gwso_sample_fwd.restype = ci
     L.gwso_sample_bwd.argtypes = [vp, i64, i64, i64, i64, i64, vp, u64, u64, vp, vp, vp]
     L.gwso_sample_bwd.restype = ci
+    L.gwso_sample_fwd_basis.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, ci, u64, u64, vp, vp]
+    L.gwso_sample_fwd_basis.restype = ci
+    L.gwso_sample_bwd_basis.argtypes = [vp, i64, i64, i64, i64, i64, vp, ci, u64, u64, vp, vp, vp]
+    L.gwso_sample_bwd_basis.restype = ci
+    L.gwso_uniform_bf16.argtypes = [ctypes.c_uint]
+    L.gwso_uniform_bf16.restype = ctypes.c_uint16
+    L.gwso_bf16_mul.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
+    L.gwso_bf16_mul.restype = ctypes.c_uint16
+    L.gwso_box_muller.argtypes = [ctypes.c_uint32, ctypes.POINTER(ctypes.c_float)]
+    L.gwso_box_muller.restype = None
+    L.gwso_box_muller_n.argtypes = [vp, vp, i64]
+    L.gwso_box_muller_n.restype = None
+    L.gwso_noise_basis.argtypes = [i64, i64, i64, i64, u64, u64, ci, vp]
+    L.gwso_noise_basis.restype = None
     L.gwso_linear_fwd.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp, vp, vp]
     L.gwso_linear_fwd.restype = ci
     L.gwso_mx_code_value.argtypes = [ci, ci]
@@ -177,10 +192,35 @@ def n_blocks(rows: int, cols: int):
     return (rows + 31) // 32, (cols + 31) // 32
 
 
+def uniform_bf16(byte: int) -> int:
+    """BF16 bits of the uniform basis value (2 * byte - 255) / 512."""
+    return int(lib().gwso_uniform_bf16(int(byte)))
+
+
+def bf16_mul(a: int, b: int) -> int:
+    return int(lib().gwso_bf16_mul(a, b))
+
+
+def box_muller(words: np.ndarray) -> np.ndarray:
+    """uint32 words -> float32 [n, 2]: the two standard normals each word gives (fp32, the oracle's defined sequence)."""
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    z = np.empty((words.size, 2), dtype=np.float32)
+    lib().gwso_box_muller_n(_ptr(words), _ptr(z), words.size)
+    return z
+
+
+def noise_basis(rows: int, cols: int, seed: int, step: int, basis: int, row0: int = 0, col0: int = 0) -> np.ndarray:
+    """R of every element under a basis, float32 [rows, cols]."""
+    r = np.empty((rows, cols), dtype=np.float32)
+    lib().gwso_noise_basis(rows, cols, row0, col0, seed, step, basis, _ptr(r))
+    return r
+
+
 def sample_fwd(w: np.ndarray, bt: np.ndarray, fmt: int, seed: int, step: int, cols: int | None = None,
-               row0: int = 0, col0: int = 0):
+               row0: int = 0, col0: int = 0, basis: int = BASIS_BITS):
     """w: uint16 [rows, ld] (BF16 bits), bt: float32 [nbr, nbc].
-    `cols` defaults to w.shape[1] (= ld).  Returns (w_hat uint16 like w, scale float32)."""
+    `cols` defaults to w.shape[1] (= ld).  Returns (w_hat uint16 like w, scale float32).
+    `basis` other than BASIS_BITS draws R from one of the comparison bases."""
     assert w.dtype == np.uint16 and w.ndim == 2 and w.flags.c_contiguous
     rows, ld = w.shape
     cols = ld if cols is None else cols
@@ -188,14 +228,18 @@ def sample_fwd(w: np.ndarray, bt: np.ndarray, fmt: int, seed: int, step: int, co
     bt = np.ascontiguousarray(bt, dtype=np.float32).reshape(nbr, nbc)
     w_hat = w.copy()  # padding columns (>= cols) keep the input bytes
     scale = np.empty((nbr, nbc), dtype=np.float32)
-    rc = lib().gwso_sample_fwd(_ptr(w), rows, cols, ld, row0, col0, _ptr(bt), fmt, seed, step, _ptr(w_hat), _ptr(scale))
+    if basis == BASIS_BITS:
+        rc = lib().gwso_sample_fwd(_ptr(w), rows, cols, ld, row0, col0, _ptr(bt), fmt, seed, step, _ptr(w_hat), _ptr(scale))
+    else:
+        rc = lib().gwso_sample_fwd_basis(_ptr(w), rows, cols, ld, row0, col0, _ptr(bt), fmt, basis, seed, step,
+                                         _ptr(w_hat), _ptr(scale))
     if rc:
         raise RuntimeError(f"gwso_sample_fwd status {rc}")
     return w_hat, scale
 
 
 def sample_bwd(g: np.ndarray, scale: np.ndarray, seed: int, step: int, cols: int | None = None,
-               row0: int = 0, col0: int = 0):
+               row0: int = 0, col0: int = 0, basis: int = BASIS_BITS):
     """g: uint16 [rows, ld].  Returns (dw uint16, dbt float64 [nbr,nbc], abs_sum float64)."""
     assert g.dtype == np.uint16 and g.ndim == 2 and g.flags.c_contiguous
     rows, ld = g.shape
@@ -205,7 +249,11 @@ def sample_bwd(g: np.ndarray, scale: np.ndarray, seed: int, step: int, cols: int
     dw = np.zeros_like(g)
     dbt = np.empty((nbr, nbc), dtype=np.float64)
     asum = np.empty((nbr, nbc), dtype=np.float64)
-    rc = lib().gwso_sample_bwd(_ptr(g), rows, cols, ld, row0, col0, _ptr(scale), seed, step, _ptr(dw), _ptr(dbt), _ptr(asum))
+    if basis == BASIS_BITS:
+        rc = lib().gwso_sample_bwd(_ptr(g), rows, cols, ld, row0, col0, _ptr(scale), seed, step, _ptr(dw), _ptr(dbt), _ptr(asum))
+    else:
+        rc = lib().gwso_sample_bwd_basis(_ptr(g), rows, cols, ld, row0, col0, _ptr(scale), basis, seed, step,
+                                         _ptr(dw), _ptr(dbt), _ptr(asum))
     if rc:
         raise RuntimeError(f"gwso_sample_bwd status {rc}")
     return dw, dbt, asum

@@ -22,7 +22,10 @@
  * blocks, Table C.1, finite differences of Eq. 3 for Eq. 4, the end points
  * of Eq. 11 and finite differences of Eq. 12; for the MX output torch's
  * float8 byte patterns, the element-format figures of the OCP Microscaling
- * specification, numpy's bit unpacking and the BF16-container output itself.
+ * specification, numpy's bit unpacking and the BF16-container output itself;
+ * for the comparison bases the exact moments of the enumerated uniform values,
+ * torch CPU bfloat16 products, the fp64 Box-Muller formula, and the cell
+ * probabilities of the rounded normal from erf.
  * Nothing here is "parity unpinned".
  */
 #include <math.h>
@@ -317,6 +320,137 @@ static int floor_log2_bf16(uint16_t a16) {
 }
 
 /* ------------------------------------------------------------------ */
+/* Alternative noise bases: the systems the paper compares GaussWS with */
+/* (Sec. 4: "DiffQ" = the same pipeline with a BF16 U(-0.5, 0.5) basis;  */
+/* Sec. 4 "Overhead": "bm" = the exact rounded normal round(N(0,1)/2)    */
+/* from a Box-Muller transform).  The paper does not say how either is   */
+/* drawn from the random integers; the readings taken here:              */
+/*  - both use the same Philox call per group of 8 elements as the bit   */
+/*    basis (same counter, same key), so only the map bits -> R differs;  */
+/*  - uniform: element k of the group takes byte (k & 3) of word k >> 2   */
+/*    and R = (2 * byte - 255) / 512: the 256 midpoints of a 1/256 grid   */
+/*    on (-0.5, 0.5), each exactly a BF16 value, mean exactly 0;          */
+/*  - Box-Muller: the pair of elements (2d, 2d+1) takes word d,           */
+/*    u1 = (low half + 0.5) / 2^16, u2 = (high half + 0.5) / 2^16,        */
+/*    z = sqrt(-2 ln u1) * (cos, sin)(2 pi u2), R = rint(z / 2) (ties to   */
+/*    even), all in fp32 as ONE defined sequence of operations (below),    */
+/*    because here floating point decides an integer.                      */
+/* With the uniform basis R * s is not exact, and the BF16 operator of    */
+/* Sec. 3.3 rounds it: PQN = bf16(R * s), w_hat = bf16(w + PQN).           */
+/* ------------------------------------------------------------------ */
+enum { GWSO_BASIS_BITS = 0, GWSO_BASIS_UNIFORM = 1, GWSO_BASIS_BOX_MULLER = 2 };
+
+static float f32_from_bits(uint32_t u) {
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+/* (2 * byte - 255) / 512 as a BF16 bit pattern (exact: an odd numerator below 256 has 8 significant bits). */
+uint16_t gwso_uniform_bf16(unsigned byte) {
+  float v = ((float)(2 * (int)(byte & 0xFFu) - 255)) / 512.0f; /* exact */
+  return (uint16_t)(f32_bits(v) >> 16);
+}
+
+/* BF16 * BF16 -> BF16, one round-to-nearest-even: the fp32 product of two 8-bit significands is exact. */
+uint16_t gwso_bf16_mul(uint16_t a, uint16_t b) {
+  return gwso_bf16_rne(bf16_to_f32(a) * bf16_to_f32(b));
+}
+
+/* ln(u) for u = (k + 0.5) / 2^16, k = 0 .. 65535, in fp32: u = m * 2^e with m in [1/sqrt2, sqrt2),
+ * ln u = e * ln2 + f * P(f), f = m - 1, P a degree-8 polynomial (Horner, fused multiply-adds).
+ * Within 2e-8 + 1 ulp of the true logarithm. */
+static float bm_log(float u) {
+  static const uint32_t cb[9] = {0x3F800000u, 0xBEFFFFFCu, 0x3EAAABC8u, 0xBE8002D3u, 0x3E4C5C05u,
+                                 0xBE2994DFu, 0x3E191428u, 0xBE13394Fu, 0x3DB31375u};
+  uint32_t ub = f32_bits(u);
+  int e = (int)(ub >> 23) - 127;
+  float m = f32_from_bits((ub & 0x007FFFFFu) | 0x3F800000u);   /* [1, 2) */
+  if (m > f32_from_bits(0x3FB504F3u)) { m = m * 0.5f; e += 1; } /* > sqrt 2 */
+  float f = m - 1.0f;                                           /* exact */
+  float p = f32_from_bits(cb[8]);
+  for (int i = 7; i >= 0; --i) p = fmaf(p, f, f32_from_bits(cb[i]));
+  return fmaf((float)e, f32_from_bits(0x3F317218u), p * f);
+}
+
+/* The two standard normals of one 32-bit word, fp32, in this order of operations:
+ *   L = -2 * ln(u1);  r = sqrt(L) (correctly rounded);
+ *   angle 2 pi u2 = q * pi/2 + pi/4 + t with q = top 2 bits of the high half, j = its low 14 bits,
+ *   t = (2 j + 1 - 16384) * fl(pi / 65536) in (-pi/4, pi/4);
+ *   sin t = t + (t * t2) * S(t2), cos t = 1 + t2 * C(t2), t2 = t * t (S degree 2, C degree 3, Horner, fma);
+ *   (c, s) = ((cos t - sin t) * fl(1/sqrt2), (cos t + sin t) * fl(1/sqrt2)), rotated by q quarter turns;
+ *   z = (r * c, r * s).                                                                             */
+void gwso_box_muller(uint32_t word, float z[2]) {
+  float u1 = ((float)(word & 0xFFFFu) + 0.5f) * f32_from_bits(0x37800000u); /* 2^-16; exact */
+  float L = -2.0f * bm_log(u1);
+  float r = sqrtf(L);
+  uint32_t hi = word >> 16, q = hi >> 14, j = hi & 0x3FFFu;
+  float t = (float)(2 * (int)j + 1 - 16384) * f32_from_bits(0x38490FDBu);
+  float t2 = t * t;
+  float sp = f32_from_bits(0xB94D6501u);
+  sp = fmaf(sp, t2, f32_from_bits(0x3C088615u));
+  sp = fmaf(sp, t2, f32_from_bits(0xBE2AAAA9u));
+  float st = fmaf(t * t2, sp, t);
+  float cp = f32_from_bits(0x37CD3809u);
+  cp = fmaf(cp, t2, f32_from_bits(0xBAB60706u));
+  cp = fmaf(cp, t2, f32_from_bits(0x3D2AAAA6u));
+  cp = fmaf(cp, t2, f32_from_bits(0xBF000000u));
+  float ct = fmaf(t2, cp, 1.0f);
+  float h = f32_from_bits(0x3F3504F3u);
+  float c = (ct - st) * h, sn = (ct + st) * h;
+  float cq, sq;
+  switch (q) {
+    case 0: cq = c; sq = sn; break;
+    case 1: cq = -sn; sq = c; break;
+    case 2: cq = -c; sq = -sn; break;
+    default: cq = sn; sq = -c; break;
+  }
+  z[0] = r * cq;
+  z[1] = r * sq;
+}
+
+void gwso_box_muller_n(const uint32_t* words, float* z, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) gwso_box_muller(words[i], z + 2 * i);
+}
+
+/* R of element k (= j & 7) of a group under a basis, from the group's four Philox words.
+ *   *r16  : R as a BF16 bit pattern (bits basis and Box-Muller: 0, +-1, +-2, with the sign bit kept on a zero)
+ * Returns R as a double (the value of *r16).                                                    */
+double gwso_basis_r(const uint32_t x[4], int k, int basis, uint16_t* r16) {
+  uint16_t out;
+  if (basis == GWSO_BASIS_UNIFORM) {
+    out = gwso_uniform_bf16((x[k >> 2] >> (8 * (k & 3))) & 0xFFu);
+  } else {
+    int mag, neg;
+    if (basis == GWSO_BASIS_BOX_MULLER) {
+      float z[2];
+      gwso_box_muller(x[k >> 1], z);
+      float rr = rintf(0.5f * z[k & 1]);           /* ties to even */
+      neg = signbit(rr) ? 1 : 0;
+      mag = (int)fabsf(rr);                        /* 0, 1 or 2: |z| < 4.86 with 16-bit u1 */
+    } else {
+      int code = element_code(x, k);
+      mag = code & 3;
+      neg = (code >> 3) & 1;
+    }
+    out = (uint16_t)((mag == 0 ? 0x0000u : (mag == 1 ? 0x3F80u : 0x4000u)) | (neg ? 0x8000u : 0u));
+  }
+  if (r16) *r16 = out;
+  return (double)bf16_to_f32(out);
+}
+
+/* R of a whole [rows x cols] tensor under a basis, as fp32 (for the statistics pins). */
+void gwso_noise_basis(int64_t rows, int64_t cols, int64_t row0, int64_t col0, uint64_t seed,
+                      uint64_t step, int basis, float* r) {
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t j = 0; j < cols; ++j) {
+      uint32_t x[4];
+      group_words(row0 + i, (col0 + j) >> 3, seed, step, x);
+      r[i * cols + j] = (float)gwso_basis_r(x, (int)((col0 + j) & 7), basis, NULL);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Forward, Eq. 3 + cast, one tensor.                                   */
 /*   w, w_hat : BF16 [rows x cols], leading dimension ld (elements)     */
 /*   bt       : fp32 [ceil(rows/32) x ceil(cols/32)]                    */
@@ -324,11 +458,11 @@ static int floor_log2_bf16(uint16_t a16) {
 /*              fp32; Eq. 4 reuses it)                                   */
 /*   row0,col0: position inside a larger tensor (multiples of 32)       */
 /* ------------------------------------------------------------------ */
-int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
-                    int64_t row0, int64_t col0, const float* bt, int fmt,
-                    uint64_t seed, uint64_t step, uint16_t* w_hat, float* scale) {
+static int sample_fwd_impl(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
+                           int64_t row0, int64_t col0, const float* bt, int fmt, int basis,
+                           uint64_t seed, uint64_t step, uint16_t* w_hat, float* scale) {
   if (!w || !bt || !w_hat || !scale) return 1;
-  if (fmt < 0 || fmt > 2) return 4;
+  if (fmt < 0 || fmt > 2 || basis < 0 || basis > 2) return 4;
   int64_t nbr = (rows + GWSO_BL - 1) / GWSO_BL, nbc = (cols + GWSO_BL - 1) / GWSO_BL;
 #pragma omp parallel for schedule(static)
   for (int64_t bi = 0; bi < nbr; ++bi) {
@@ -363,6 +497,12 @@ int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
            * so R = "-0" gives -0.0 (Sec. 3.4: sign-mantissa reconstruction) */
           uint16_t pqn = (uint16_t)((mag == 0 ? 0u : (mag == 1 ? s16 : s2_16)) |
                                     ((code & 8) ? 0x8000u : 0u));
+          if (basis != GWSO_BASIS_BITS) {
+            /* another basis: PQN = bf16(R * s), which is exact for R in {0, +-1, +-2} */
+            uint16_t r16;
+            gwso_basis_r(x, (int)(j & 7), basis, &r16);
+            pqn = gwso_bf16_mul(r16, s16);
+          }
           uint16_t sum = gwso_bf16_add(w[i * ld + j], pqn);
           w_hat[i * ld + j] = (a16 == 0) ? sum : gwso_cast(sum, Ea, fmt);
         }
@@ -370,6 +510,19 @@ int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
     }
   }
   return 0;
+}
+
+int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
+                    int64_t row0, int64_t col0, const float* bt, int fmt,
+                    uint64_t seed, uint64_t step, uint16_t* w_hat, float* scale) {
+  return sample_fwd_impl(w, rows, cols, ld, row0, col0, bt, fmt, GWSO_BASIS_BITS, seed, step, w_hat, scale);
+}
+
+/* The same forward pass with R drawn from another basis (see the bases above). */
+int gwso_sample_fwd_basis(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
+                          int64_t row0, int64_t col0, const float* bt, int fmt, int basis,
+                          uint64_t seed, uint64_t step, uint16_t* w_hat, float* scale) {
+  return sample_fwd_impl(w, rows, cols, ld, row0, col0, bt, fmt, basis, seed, step, w_hat, scale);
 }
 
 /* ------------------------------------------------------------------ */
@@ -380,10 +533,11 @@ int gwso_sample_fwd(const uint16_t* w, int64_t rows, int64_t cols, int64_t ld,
 /*   abs_sum : out fp64 per block (may be NULL), ln2 * s32 * sum|g .* R|,*/
 /*             the scale of rounding error a fp32 reduction may show     */
 /* ------------------------------------------------------------------ */
-int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
-                    int64_t row0, int64_t col0, const float* scale, uint64_t seed,
-                    uint64_t step, uint16_t* dw, double* dbt, double* abs_sum) {
+static int sample_bwd_impl(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
+                           int64_t row0, int64_t col0, const float* scale, int basis, uint64_t seed,
+                           uint64_t step, uint16_t* dw, double* dbt, double* abs_sum) {
   if (!g || !scale || !dbt) return 1;
+  if (basis < 0 || basis > 2) return 4;
   int64_t nbr = (rows + GWSO_BL - 1) / GWSO_BL, nbc = (cols + GWSO_BL - 1) / GWSO_BL;
   const double ln2 = 0.69314718055994530942;
 #pragma omp parallel for schedule(static)
@@ -397,8 +551,9 @@ int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
         for (int64_t j = j0; j < j1; ++j) {
           uint32_t x[4];
           group_words(row0 + i, (col0 + j) >> 3, seed, step, x);
-          int r = gwso_code_to_r(element_code(x, (int)(j & 7)));
-          double term = (double)bf16_to_f32(g[i * ld + j]) * (double)r;
+          double r = (double)gwso_code_to_r(element_code(x, (int)(j & 7)));
+          if (basis != GWSO_BASIS_BITS) r = gwso_basis_r(x, (int)(j & 7), basis, NULL);
+          double term = (double)bf16_to_f32(g[i * ld + j]) * r;
           acc += term;
           aacc += fabs(term);
           if (dw) dw[i * ld + j] = g[i * ld + j];
@@ -409,6 +564,19 @@ int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
     }
   }
   return 0;
+}
+
+int gwso_sample_bwd(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
+                    int64_t row0, int64_t col0, const float* scale, uint64_t seed,
+                    uint64_t step, uint16_t* dw, double* dbt, double* abs_sum) {
+  return sample_bwd_impl(g, rows, cols, ld, row0, col0, scale, GWSO_BASIS_BITS, seed, step, dw, dbt, abs_sum);
+}
+
+/* Eq. 4 with R drawn from another basis. */
+int gwso_sample_bwd_basis(const uint16_t* g, int64_t rows, int64_t cols, int64_t ld,
+                          int64_t row0, int64_t col0, const float* scale, int basis, uint64_t seed,
+                          uint64_t step, uint16_t* dw, double* dbt, double* abs_sum) {
+  return sample_bwd_impl(g, rows, cols, ld, row0, col0, scale, basis, seed, step, dw, dbt, abs_sum);
 }
 
 /* ------------------------------------------------------------------ */

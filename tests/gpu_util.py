@@ -10,7 +10,8 @@ from paper_2505_11170_amd import synth
 DEV = "cuda:0"
 # Largest share of blocks for which the additive rounding floor of assert_dbt_close, not its 1e-5 relative
 # term, may be what accepts the GPU's dL/db_t (blocks whose 1024 signed terms cancel almost completely).
-CANCELLATION_SHARE = 0.10
+# Measured: 23 of 946 176 blocks (1B model), 7 of 248 832 (GPT2-124M, three steps).
+CANCELLATION_SHARE = 2e-4
 
 
 def ensure_built():

@@ -25,8 +25,10 @@ from gpu_util import DEV, ensure_built
 
 pytestmark = pytest.mark.gpu
 
-# block maxima as BF16 bit patterns: 1.0, ~0.0201 (odd mantissa), 1.75, 0.0622 (mantissa all ones), 2^-100, 2^40
-MAXIMA = [0x3F80, 0x3CA5, 0x3FE0, 0x3D7F, 0x0D80, 0x5380]
+# block maxima as BF16 bit patterns: 1.0, ~0.0201 (odd mantissa), 1.75, 0.0622 (mantissa all ones), 2^-99, 2^40.
+# (2^-99 and not the 2^-100 that bounds the supported domain: in the ragged copy an edge block can lose its planted
+# maximum, and the largest remaining pattern must still lie in the domain.)
+MAXIMA = [0x3F80, 0x3CA5, 0x3FE0, 0x3D7F, 0x0E00, 0x5380]
 BITWIDTHS = [60.0, 6.0, 2.0, 1.0]
 NBC = 8                                   # blocks per block row: 256 columns = one workgroup tile
 
@@ -86,8 +88,8 @@ def test_every_bf16_pattern_through_the_cast(sweep, fmt, ragged):
     scale = torch.full((nbr, nbc), float("nan"), device=DEV)
     d = gws.TensorDesc(rows=rows, cols=cols, ld=ld, seed=seed, w=w, w_hat=w_hat, bt=bt, scale=scale)
     gws.gws_sample_fwd([d], fmt, step)
-    ldc = oracle.mx_row_bytes(cols, fmt) + (8 if fmt == gws.FMT_FP8_E4M3 else 2)
-    ldc = (ldc + 7) // 8 * 8 if fmt == gws.FMT_FP8_E4M3 else ldc
+    ldc = oracle.mx_row_bytes(cols, fmt) + 8                               # padded rows: FP8 a multiple of 8, FP6 of 2
+    ldc = (ldc + 7) // 8 * 8 if fmt == gws.FMT_FP8_E4M3 else (ldc + 1) // 2 * 2
     codes = torch.full((rows, ldc), 0xAA, dtype=torch.uint8, device=DEV)
     xscale = torch.zeros(nbr, nbc, dtype=torch.uint8, device=DEV)
     scale_mx = torch.full((nbr, nbc), float("nan"), device=DEV)
@@ -96,6 +98,8 @@ def test_every_bf16_pattern_through_the_cast(sweep, fmt, ragged):
     torch.cuda.synchronize()
 
     ref_q, ref_s = oracle.sample_fwd(w_np, bt_np, fmt, seed, step, cols=cols)
+    amax = np.array([[(w_np[i * 32:i * 32 + 32, j * 32:min(cols, j * 32 + 32)] & 0x7FFF).max() for j in range(nbc)] for i in range(nbr)])
+    assert amax.min() >= 0x0D80                                             # every block inside the supported domain
     got = synth.bits(w_hat)
     bad = np.argwhere(got != ref_q)
     assert len(bad) == 0, [(int(i), int(j), hex(w_np[i, j]), float(bt_np[i // 32, j // 32]), hex(got[i, j]), hex(ref_q[i, j]))

@@ -12,6 +12,7 @@ import pytest
 
 import oracle
 import test_oracle_arith as arith
+import test_oracle_basis as basis
 import test_oracle_bitwidth as bw
 import test_oracle_mx as mx
 import test_oracle_rng as rng
@@ -83,8 +84,8 @@ MUTANTS = [
      [smp.test_backward_matches_finite_difference_of_eq3]),
     ("backward: dW not a copy", "if (dw) dw[i * ld + j] = g[i * ld + j];", "if (dw) dw[i * ld + j] = g[i * ld + j] ^ 0x8000u;",
      [smp.test_backward_dw_is_g_and_dbt_matches_definition]),
-    ("backward: different noise than forward", "group_words(row0 + i, (col0 + j) >> 3, seed, step, x);\n          int r =",
-     "group_words(row0 + i, (col0 + j) >> 3, seed, step + 1, x);\n          int r =",
+    ("backward: different noise than forward", "group_words(row0 + i, (col0 + j) >> 3, seed, step, x);\n          double r =",
+     "group_words(row0 + i, (col0 + j) >> 3, seed, step + 1, x);\n          double r =",
      [smp.test_backward_matches_finite_difference_of_eq3]),
     ("linear: weight layout flag inverted", "w_is_nk ? q[n * ldq + k] : q[k * ldq + n]", "w_is_nk ? q[k * ldq + n] : q[n * ldq + k]",
      [smp.test_linear_vs_numpy_fp64_matmul]),
@@ -94,6 +95,27 @@ MUTANTS = [
      "if (rem >= half) keep += 1;\n  int ef", [smp.test_linear_bf16_output_rounds_once_to_nearest_even]),
     ("linear: subnormal Y flushed to zero", "if (E < -126) drop += (-126 - E);", "if (E < -126) return (uint16_t)(sign << 15);",
      [smp.test_linear_bf16_output_rounds_once_to_nearest_even]),
+    ("uniform basis: grid shifted by half a step", "2 * (int)(byte & 0xFFu) - 255", "2 * (int)(byte & 0xFFu) - 256",
+     [basis.test_uniform_values_enumerated]),
+    ("uniform basis: element takes the wrong byte", "(x[k >> 2] >> (8 * (k & 3)))", "(x[k & 3] >> (8 * (k >> 2)))",
+     [basis.test_uniform_element_owns_byte_k_mod_4_of_word_k_div_4]),
+    ("uniform basis: R * s truncated instead of rounded", "return gwso_bf16_rne(bf16_to_f32(a) * bf16_to_f32(b));",
+     "return (uint16_t)(f32_bits(bf16_to_f32(a) * bf16_to_f32(b)) >> 16);", [basis.test_bf16_mul_matches_torch]),
+    ("Box-Muller: sine and cosine branches swapped", "z[0] = r * cq;\n  z[1] = r * sq;", "z[0] = r * sq;\n  z[1] = r * cq;",
+     [basis.test_box_muller_matches_the_fp64_formula]),
+    ("Box-Muller: radius from -ln instead of -2 ln", "float L = -2.0f * bm_log(u1);", "float L = -1.0f * bm_log(u1);",
+     [basis.test_box_muller_matches_the_fp64_formula]),
+    ("Box-Muller: second quadrant mirrored", "case 1: cq = -sn; sq = c; break;", "case 1: cq = sn; sq = c; break;",
+     [basis.test_box_muller_matches_the_fp64_formula]),
+    ("Box-Muller: logarithm coefficient", "0x3EAAABC8u", "0x3EABABC8u", [basis.test_box_muller_matches_the_fp64_formula]),
+    ("Box-Muller: round(z) instead of round(z / 2)", "float rr = rintf(0.5f * z[k & 1]);", "float rr = rintf(z[k & 1]);",
+     [basis.test_box_muller_cells_match_the_rounded_normal]),
+    ("Box-Muller: pair takes the wrong word", "gwso_box_muller(x[k >> 1], z);", "gwso_box_muller(x[k >> 2], z);",
+     [basis.test_box_muller_pair_d_takes_word_d_cos_then_sin]),
+    ("basis forward: step doubled", "pqn = gwso_bf16_mul(r16, s16);", "pqn = gwso_bf16_mul(r16, s2_16);",
+     [lambda: basis.test_forward_with_a_basis_vs_library_composition(oracle.BASIS_UNIFORM, (70, 45))]),
+    ("basis backward: falls back to the bit basis", "if (basis != GWSO_BASIS_BITS) r = gwso_basis_r", "if (0) r = gwso_basis_r",
+     [lambda: basis.test_backward_with_a_basis_matches_the_definition(oracle.BASIS_BOX_MULLER)]),
     ("Eq. 11: offset is b_init instead of b_target", "bt[k] = b_target + prod;", "bt[k] = b_init + prod;",
      [bw.test_eq11_end_points_and_midpoint]),
     ("Eq. 11: slope sign", "float delta = b_init - b_target;\n  for (int64_t k = 0; k < n; ++k) {\n    float prod = bi[k] * delta;\n    bt[k]",
