@@ -3,7 +3,8 @@
  *
  * C ABI.  Every pointer named "device" is HIP device memory owned by the caller;
  * every other pointer is host memory.  The library allocates no device memory,
- * keeps no global state and is thread-safe.  All GPU work is enqueued
+ * keeps no global state (one exception is stated at gws_linear_fwd_static) and is
+ * thread-safe.  All GPU work is enqueued
  * asynchronously on the given stream (a hipStream_t passed as void*, NULL = the
  * default stream); no call synchronises.
  * The return value is a gws_status and reports argument and launch errors only;
@@ -55,7 +56,8 @@ typedef enum gws_status {
   GWS_ERR_ALIGN = 3,  /* BF16 pointer not 16-byte aligned, fp32 pointer not 4-byte */
   GWS_ERR_FORMAT = 4, /* unknown gws_format                                      */
   GWS_ERR_LAUNCH = 5, /* the HIP runtime refused a kernel launch                 */
-  GWS_ERR_ALIAS = 6   /* an output overlaps an input it must not overlap         */
+  GWS_ERR_ALIAS = 6,  /* an output overlaps an input it must not overlap         */
+  GWS_ERR_TOO_LARGE = 7 /* the operand exceeds a fixed capacity of the library (gws_linear_fwd_static) */
 } gws_status;
 
 /* One weight tensor, row-major.  BF16 buffers are [rows x ld] with ld >= cols
@@ -196,6 +198,22 @@ size_t gws_linear_fwd_workspace_bytes(const gws_tensor* w);
 int gws_linear_fwd_ws(const void* x, int64_t M, int64_t K, int64_t ldx,
                       const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
                       void* y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* gws_linear_fwd_ws for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It allocates
+ * nothing and takes no workspace: w_hat and scale are staged in a buffer of GWS_STATIC_SCRATCH_BYTES
+ * that is part of the loaded library (every GPU the library runs on holds its own copy until the
+ * process ends; its address on a GPU is looked up on the first call made with that GPU current).
+ * Same arguments, same results (Y bit-identical) as gws_linear_fwd_ws.
+ *   - a weight with gws_linear_fwd_workspace_bytes(w) > GWS_STATIC_SCRATCH_BYTES is rejected with
+ *     GWS_ERR_TOO_LARGE and nothing is launched;
+ *   - all calls on one GPU share that GPU's buffer, which keeps the last call's contents: calls
+ *     that overlap in time on one GPU (different streams, or threads) race on it; calls on one
+ *     stream are ordered and safe.  This is the library's only state.                          */
+#define GWS_STATIC_SCRATCH_BYTES (32u << 20)
+int gws_linear_fwd_static(const void* x, int64_t M, int64_t K, int64_t ldx,
+                          const gws_tensor* w, int w_is_nk, int fmt, uint64_t step,
+                          void* y, int64_t ldy, void* stream);
 
 /* Weight gradient of the sampled-weight linear with the reduction of Eq. 4 in the GEMM's
  * epilogue (the linear's backward pass, paper Eq. 2, applied to w_hat):

@@ -19,7 +19,7 @@ LINEAR_AUTO, LINEAR_IN_OPERAND, LINEAR_TWO_KERNELS = 0, 2, 3
 
 # include/gws.h (the method) and include/gws_bench.h (measurement aids)
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode",
-           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
+           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
            "gws_derive_seed", "gws_status_string", "gws_version")
 BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax")
 
@@ -118,6 +118,8 @@ def load_library() -> ctypes.CDLL:
     L.gws_linear_fwd_mode.restype = ci
     L.gws_linear_fwd_ws.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp, ctypes.c_size_t, vp]
     L.gws_linear_fwd_ws.restype = ci
+    L.gws_linear_fwd_static.argtypes = [vp, i64, i64, i64, tp, ci, ci, u64, vp, i64, vp]
+    L.gws_linear_fwd_static.restype = ci
     L.gws_linear_fwd_workspace_bytes.argtypes = [tp]
     L.gws_linear_fwd_workspace_bytes.restype = ctypes.c_size_t
     L.gws_gemm_bf16_sample_next.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, tp, ci, u64, vp]
@@ -314,6 +316,17 @@ def gws_linear_fwd_ws(x, w: TensorDesc, y, fmt: int, step: int, workspace, w_is_
     _check(L.gws_linear_fwd_ws(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt), int(step),
                                _p(y), int(y.stride(0)), _p(workspace), int(workspace.numel() * workspace.element_size()),
                                _stream(stream)), "gws_linear_fwd_ws")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def gws_linear_fwd_static(x, w: TensorDesc, y, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:
+    """``gws_linear_fwd_ws`` without a workspace and without any allocation: w_hat is staged in the library's own buffer."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    _check(L.gws_linear_fwd_static(_p(x), M, K, int(x.stride(0)), _marshal([w]), int(bool(w_is_nk)), int(fmt), int(step),
+                                   _p(y), int(y.stride(0)), _stream(stream)), "gws_linear_fwd_static")
 
 
 def gws_linear_bwd_w(x, dy, w: TensorDesc, step: int, w_is_nk: bool = False, stream=None) -> None:

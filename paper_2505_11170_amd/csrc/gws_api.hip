@@ -2,12 +2,35 @@
 // the meaning of every argument are in include/gws.h.
 #include <string.h>
 
+#include <atomic>
+
 #include "gws_bench.h"
 #include "gws_launch.h"
+
+// Staging buffer of gws_linear_fwd_static: device memory that belongs to the loaded code object, one copy
+// per GPU.  Host code never uses this name as an address: it asks the runtime for the device address
+// (scratch_of_current_device) and passes that to the kernels like any other buffer.
+static __device__ __align__(256) unsigned char scratch[GWS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 using namespace gws;
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];   // device address of `scratch` on each GPU, once looked up
+
+// The address of `scratch` on the current device (looked up once per device, with that device current).
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GWS_ERR_LAUNCH;
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return GWS_ERR_LAUNCH;
+    g_scratch_addr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return GWS_OK;
+}
 
 inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -375,6 +398,19 @@ int gws_linear_fwd_ws(const void* x, int64_t M, int64_t K, int64_t ldx, const gw
   return linear_staged(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, workspace, (hipStream_t)stream);
 }
 
+int gws_linear_fwd_static(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
+                          int fmt, uint64_t step, void* y, int64_t ldy, void* stream) {
+  if (!w) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  int rc = check_linear(x, M, K, ldx, w, w_is_nk, y, ldy);
+  if (rc != GWS_OK || M == 0 || (w_is_nk ? w->rows : w->cols) == 0) return rc;
+  if (gws_linear_fwd_workspace_bytes(w) > (size_t)GWS_STATIC_SCRATCH_BYTES) return GWS_ERR_TOO_LARGE;
+  void* staging = nullptr;
+  rc = scratch_of_current_device(&staging);
+  if (rc != GWS_OK) return rc;
+  return linear_staged(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, staging, (hipStream_t)stream);
+}
+
 int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_tensor* w, int w_is_nk,
                    int fmt, uint64_t step, void* y, int64_t ldy, void* stream) {
   return gws_linear_fwd_mode(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, GWS_LINEAR_AUTO, stream);
@@ -507,10 +543,11 @@ const char* gws_status_string(int status) {
     case GWS_ERR_FORMAT: return "unknown target format";
     case GWS_ERR_LAUNCH: return "kernel launch failed";
     case GWS_ERR_ALIAS: return "output overlaps input";
+    case GWS_ERR_TOO_LARGE: return "operand exceeds a fixed capacity of the library";
     default: return "unknown status";
   }
 }
 
-int gws_version(void) { return 6; }
+int gws_version(void) { return 7; }
 
 }  // extern "C"

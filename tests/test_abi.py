@@ -103,6 +103,14 @@ def test_argument_validation_launches_nothing(lib):
     assert lib.gws_linear_fwd_ws(*lin, fake, need, None) == ALIAS                                  # workspace on w
     assert lib.gws_linear_fwd_ws(*lin, fake + 0x500000, need, None) == ALIAS                       # workspace on y
     assert lib.gws_linear_fwd_ws(fake, 0, 64, 64, wdesc, 0, 1, 0, fake, 64, None, 0, None) == OK   # empty
+    # the allocation-free form: same argument rules; a weight beyond the library's staging buffer is refused
+    TOO_LARGE = 7
+    assert lib.gws_linear_fwd_static(None, 8, 64, 64, wdesc, 0, 1, 0, fake + 0x500000, 64, None) == NULL
+    assert lib.gws_linear_fwd_static(fake + 0x300000, 8, 32, 32, wdesc, 0, 1, 0, fake + 0x500000, 64, None) == SHAPE
+    assert lib.gws_linear_fwd_static(fake, 0, 64, 64, wdesc, 0, 1, 0, fake, 64, None) == OK        # empty
+    big = (_CTensor * 1)(_t(**{**base, "rows": 4096, "cols": 4096 + 32, "ld": 4096 + 32}))         # 33 MiB of w_hat
+    assert lib.gws_linear_fwd_workspace_bytes(big) > 32 << 20
+    assert lib.gws_linear_fwd_static(fake + 0x300000, 8, 4096, 4096, big, 0, 1, 0, fake + 0x500000, 4128, None) == TOO_LARGE
     assert lib.gws_gemm_bf16(fake, 8, 48, 48, fake, 64, 64, 0, fake, 64, None) == SHAPE      # K % 32
     assert lib.gws_gemm_bf16(None, 8, 64, 64, fake, 64, 64, 0, fake, 64, None) == NULL
     assert lib.gws_gemm_bf16(fake, 0, 64, 64, fake, 64, 64, 0, fake, 64, None) == OK         # empty
@@ -116,7 +124,7 @@ def test_argument_validation_launches_nothing(lib):
     assert lib.gws_gemm_bf16_sample_next(*gemm, (_CTensor * 1)(_t(**{**base, "w_hat": fake + 0x800040})), 1, 0, None) == ALIAS
     assert lib.gws_gemm_bf16_sample_next(fake, 256, 48, 48, fake + 0x400000, 256, 256, 0, fake + 0x800000, 256, nxt, 1, 0, None) == SHAPE
     assert lib.gws_gemm_bf16_sample_next(None, 256, 64, 64, fake + 0x400000, 256, 256, 0, fake + 0x800000, 256, nxt, 1, 0, None) == NULL
-    for s in range(7):
+    for s in range(8):
         assert lib.gws_status_string(s)
 
 
