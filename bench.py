@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="run only the precision x format sweep of config 4 and print its JSON")
+    ap.add_argument("--only-bases", action="store_true",
+                    help="run only the noise-basis comparison (forward unit benchmark) and print its JSON")
     ap.add_argument("--only-linear", action="store_true",
                     help="run only the fused-linear comparison (config 5) and print its JSON (for profiling)")
     ap.add_argument("--calibrate", action="store_true",
@@ -133,6 +135,11 @@ def main():
 
     if args.only_linear:
         print(json.dumps({"fused_linear": linear_bench(torch, gws, synth, dev)}))
+        return
+    if args.only_bases:
+        sh = synth.llama_1b_shapes()
+        print(json.dumps({"noise_bases_forward_unit_benchmark": basis_bench(torch, gws, synth, dev),
+                          "noise_bases_fwd_bwd_llama_1b": basis_step_bench(torch, gws, synth, dev, sh, sum(s.rows * s.cols for s in sh))}))
         return
 
     if args.sweep:
@@ -251,6 +258,11 @@ def main():
             extras["mx_output"] = mx_bench(torch, gws, synth, dev, shapes, params)
         except Exception as e:  # pragma: no cover
             extras["mx_output_error"] = repr(e)
+        try:
+            extras["noise_bases_forward_unit_benchmark"] = basis_bench(torch, gws, synth, dev)
+            extras["noise_bases_fwd_bwd_" + args.workload] = basis_step_bench(torch, gws, synth, dev, shapes, params)
+        except Exception as e:  # pragma: no cover
+            extras["noise_bases_error"] = repr(e)
         try:
             extras["copy_ceiling"] = copy_ceiling(torch)
             extras["fused_linear"] = linear_bench(torch, gws, synth, dev)
@@ -471,6 +483,65 @@ def mx_bench(torch, gws, synth, dev, shapes, params):
                      "GBps": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS}
         del sets
         torch.cuda.empty_cache()
+    return out
+
+
+def basis_bench(torch, gws, synth, dev):
+    """The shape of the paper's forward unit benchmark (Sec. 4 "Overhead", Fig. 7: Eq. 3 on a matrix w_(M,N), in
+    10^9 elements/s, "ours" against a Box-Muller rounded normal) on this hardware, plus the BF16 uniform basis of
+    the paper's DiffQ extension: gws_sample_fwd against gws_sample_fwd_basis, BF16 target as in the paper's runs.
+    Shapes: the ends of the ranges the paper names for Llama 3.2 1B and Llama 3.1 405B weights."""
+    out = {}
+    bases = (("ours_bits", gws.BASIS_BITS), ("box_muller", gws.BASIS_BOX_MULLER), ("uniform_bf16", gws.BASIS_UNIFORM_BF16))
+    for rows, cols in ((2048, 512), (2048, 2048), (2048, 8192), (16384, 1024), (16384, 16384)):
+        n_buf = max(2, min(8, int(6e8 // (rows * cols * 4)) + 1))        # rotate past the last-level cache where that is cheap
+        packs = []
+        for k in range(n_buf):
+            t = synth.make_tensor(40 + k, rows, cols, device=dev, with_grad=False)
+            packs.append(gws.pack([gws.TensorDesc(rows=rows, cols=cols, seed=gws.gws_derive_seed(1, k), w=t["w"],
+                                                  w_hat=torch.empty_like(t["w"]), bt=t["bt"],
+                                                  scale=torch.empty(rows // 32, cols // 32, device=dev))]))
+        cell = {}
+        for name, basis in bases:
+            k = [0]
+
+            def fn():
+                k[0] += 1
+                gws.gws_sample_fwd_basis(packs[k[0] % n_buf], basis, gws.FMT_BF16, k[0])
+            iters = 200 if rows * cols < 1 << 24 else 30
+            ms = _time_ms(torch, fn, iters, warmup=10)
+            cell[name] = {"us_per_call": ms * 1e3, "gelem_per_s": rows * cols / ms / 1e6}
+        cell["box_muller_over_ours"] = cell["box_muller"]["us_per_call"] / cell["ours_bits"]["us_per_call"]
+        cell["uniform_over_ours"] = cell["uniform_bf16"]["us_per_call"] / cell["ours_bits"]["us_per_call"]
+        out[f"{rows}x{cols}"] = cell
+        del packs
+        torch.cuda.empty_cache()
+    return out
+
+
+def basis_step_bench(torch, gws, synth, dev, shapes, params):
+    """fwd+bwd over a whole workload per noise basis (what the paper's Table 1 contrasts as GaussWS against DiffQ,
+    there inside a training step)."""
+    out = {}
+    descs = []
+    for i, sh in enumerate(shapes):
+        t = synth.make_tensor(i, sh.rows, sh.cols, device=dev)
+        nbr, nbc = synth.n_blocks(sh.rows, sh.cols)
+        descs.append(gws.TensorDesc(rows=sh.rows, cols=sh.cols, seed=gws.gws_derive_seed(0, i), w=t["w"], w_hat=torch.empty_like(t["w"]),
+                                    bt=t["bt"], scale=torch.empty(nbr, nbc, device=dev), g=t["g"], dw=t["g"],
+                                    dbt=torch.empty(nbr, nbc, device=dev)))
+    pk = gws.pack(descs)
+    for name, basis in (("ours_bits", gws.BASIS_BITS), ("box_muller", gws.BASIS_BOX_MULLER), ("uniform_bf16", gws.BASIS_UNIFORM_BF16)):
+        k = [0]
+
+        def fn():
+            k[0] += 1
+            gws.gws_sample_fwd_basis(pk, basis, gws.FMT_FP8_E4M3, k[0])
+            gws.gws_sample_bwd_basis(pk, basis, k[0])
+        ms = _time_ms(torch, fn, 30, warmup=10)
+        out[name] = {"ms_per_step": ms, "params_per_s": params / ms * 1e3}
+    out["box_muller_over_ours"] = out["box_muller"]["ms_per_step"] / out["ours_bits"]["ms_per_step"]
+    out["uniform_over_ours"] = out["uniform_bf16"]["ms_per_step"] / out["ours_bits"]["ms_per_step"]
     return out
 
 

@@ -253,6 +253,33 @@ int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx,
                               void* y, int64_t ldy,
                               const gws_tensor* next, int fmt, uint64_t step, void* stream);
 
+/* The comparison systems of the paper's Sec. 4 behind the same interface: the same forward and
+ * backward passes with R drawn from another noise basis.  The paper compares GaussWS with the same
+ * pipeline on a BF16 U(-0.5, 0.5) basis (its "DiffQ" extension, Sec. 4 and Table 1) and, in the
+ * forward unit benchmark (Sec. 4 "Overhead"), with the exact rounded normal round(N(0,1)/2) from a
+ * Box-Muller transform ("bm"); it does not say how either is drawn from the random integers.  Here
+ * both use the Philox call of the bit basis (same counter, same key) per group of 8 elements:
+ *   GWS_BASIS_UNIFORM_BF16  element k (= j & 7) owns byte k % 4 of word k / 4;
+ *                           R = (2 byte - 255) / 512, the 256 midpoints of a 1/256 grid on
+ *                           (-0.5, 0.5): BF16 values, mean exactly 0, variance (1 - 2^-16) / 12.
+ *                           R * s is not exact and is rounded to BF16 before the add:
+ *                           w_hat = cast_fmt( bf16_rne( w + bf16_rne(R * s) ) ).
+ *   GWS_BASIS_BOX_MULLER    the pair of elements (2d, 2d + 1) owns word d; u1 = (low half + 0.5) / 2^16,
+ *                           u2 = (high half + 0.5) / 2^16, z = sqrt(-2 ln u1) (cos, sin)(2 pi u2) in
+ *                           fp32 (one fixed sequence of operations), R = rint(z / 2) in {0, +-1, +-2}.
+ *   GWS_BASIS_BITS          the method's own basis (Sec. 3.4): gws_sample_fwd / gws_sample_bwd.
+ * Everything else (block maximum, scale, cast, Eq. 4 with this R) is as in gws_sample_fwd /
+ * gws_sample_bwd; an unknown basis gives GWS_ERR_FORMAT.                                        */
+typedef enum gws_basis { GWS_BASIS_BITS = 0, GWS_BASIS_UNIFORM_BF16 = 1, GWS_BASIS_BOX_MULLER = 2 } gws_basis;
+int gws_sample_fwd_basis(const gws_tensor* t, int n, int basis, int fmt, uint64_t step, void* stream);
+int gws_sample_bwd_basis(const gws_tensor* t, int n, int basis, uint64_t step, void* stream);
+
+/* R of a comparison basis alone: out is device BF16 [rows x cols] (cols and col0 multiples of 8,
+ * out 16-byte aligned), every R being a BF16 value (the Box-Muller basis keeps the sign on a zero).
+ * basis is GWS_BASIS_UNIFORM_BF16 or GWS_BASIS_BOX_MULLER (the bit basis has gws_noise_packed).   */
+int gws_noise_basis(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0,
+                    uint64_t seed, uint64_t step, int basis, void* stream);
+
 /* The packed noise alone (paper Sec. 3.4: sign-magnitude, 4 bits per element,
  * 8 elements per 32-bit word): out is device u32 [rows x ceil(cols/8)], element
  * k of a group in bits 4k..4k+3, code = sign<<3 | |R|.  The training path never

@@ -442,6 +442,7 @@ double gwso_basis_r(const uint32_t x[4], int k, int basis, uint16_t* r16) {
 /* R of a whole [rows x cols] tensor under a basis, as fp32 (for the statistics pins). */
 void gwso_noise_basis(int64_t rows, int64_t cols, int64_t row0, int64_t col0, uint64_t seed,
                       uint64_t step, int basis, float* r) {
+#pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < rows; ++i)
     for (int64_t j = 0; j < cols; ++j) {
       uint32_t x[4];

@@ -16,10 +16,12 @@ _LIB_PATH = os.environ.get("GWS_LIBRARY") or os.path.join(_HERE, "libgws.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP6_E3M2 = 0, 1, 2
 LINEAR_AUTO, LINEAR_IN_OPERAND, LINEAR_TWO_KERNELS = 0, 2, 3
+BASIS_BITS, BASIS_UNIFORM_BF16, BASIS_BOX_MULLER = 0, 1, 2
 
 # include/gws.h (the method) and include/gws_bench.h (measurement aids)
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode",
            "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
+           "gws_sample_fwd_basis", "gws_sample_bwd_basis", "gws_noise_basis",
            "gws_derive_seed", "gws_status_string", "gws_version")
 BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax")
 
@@ -132,6 +134,12 @@ def load_library() -> ctypes.CDLL:
     L.gws_linear_bwd_w.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
     L.gws_gemm_bf16.restype = ci
+    L.gws_sample_fwd_basis.argtypes = [tp, ci, ci, ci, u64, vp]
+    L.gws_sample_fwd_basis.restype = ci
+    L.gws_sample_bwd_basis.argtypes = [tp, ci, ci, u64, vp]
+    L.gws_sample_bwd_basis.restype = ci
+    L.gws_noise_basis.argtypes = [vp, i64, i64, i64, i64, u64, u64, ci, vp]
+    L.gws_noise_basis.restype = ci
     L.gws_noise_packed.argtypes = [vp, i64, i64, i64, i64, u64, u64, vp]
     L.gws_noise_packed.restype = ci
     L.gws_derive_seed.argtypes = [u64, u64]
@@ -368,6 +376,28 @@ def gws_block_absmax(t: Sequence[TensorDesc], stream=None) -> None:
     L = load_library()
     arr, n = _as_c(t)
     _check(L.gws_block_absmax(arr, n, _stream(stream)), "gws_block_absmax")
+
+
+def gws_sample_fwd_basis(t: Sequence[TensorDesc], basis: int, fmt: int, step: int, stream=None) -> None:
+    """``gws_sample_fwd`` with R drawn from a comparison basis (``BASIS_*``; paper Sec. 4)."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_fwd_basis(arr, n, int(basis), int(fmt), int(step), _stream(stream)), "gws_sample_fwd_basis")
+
+
+def gws_sample_bwd_basis(t: Sequence[TensorDesc], basis: int, step: int, stream=None) -> None:
+    """``gws_sample_bwd`` with R drawn from a comparison basis."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_bwd_basis(arr, n, int(basis), int(step), _stream(stream)), "gws_sample_bwd_basis")
+
+
+def gws_noise_basis(out, rows: int, cols: int, seed: int, step: int, basis: int, row0: int = 0, col0: int = 0,
+                    stream=None) -> None:
+    """R of a comparison basis as BF16 values into ``out`` [rows, cols]."""
+    L = load_library()
+    _check(L.gws_noise_basis(_p(out), rows, cols, row0, col0, seed & (2 ** 64 - 1), int(step), int(basis),
+                             _stream(stream)), "gws_noise_basis")
 
 
 def gws_noise_packed(out, rows: int, cols: int, seed: int, step: int, row0: int = 0, col0: int = 0,

@@ -112,8 +112,9 @@ constexpr int kAbsmaxOnly = -2;  // the backward launch shape, block-maximum ker
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 // `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
 // `mx` (one per tensor, forward only) switches the output to MX element codes and block scales.
+// `basis` other than kBasisBits runs the sampling passes on a comparison noise basis (no bw, no mx then).
 int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx_out* mx, bool fwd, int fmt,
-                uint64_t step, hipStream_t stream, bool keep = false) {
+                uint64_t step, hipStream_t stream, bool keep = false, int basis = kBasisBits) {
   // Tiles per workgroup.  Forward: one (most workgroups, fewest registers; measured best).
   // Backward does less per tile, so the per-wavefront set-up shows: a workgroup takes up to
   // four neighbouring column tiles while at least ~3000 workgroups (12 per compute unit)
@@ -142,9 +143,11 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   auto flush = [&]() -> int {
     if (a.n == 0) return GWS_OK;
     int rc = (!fwd && fmt == kAbsmaxOnly) ? launch_block_absmax(a, (uint32_t)wgs, stream)
+             : (!fwd && basis != kBasisBits) ? launch_sample_bwd_basis(a, (uint32_t)wgs, basis, stream)
              : !fwd ? launch_sample_bwd(a, (uint32_t)wgs, stream)
              : fmt == kCopyOnly ? launch_copy_tiles(a, (uint32_t)wgs, stream)
-                                : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, keep, stream);
+             : basis != kBasisBits ? launch_sample_fwd_basis(a, (uint32_t)wgs, fmt, keep, basis, stream)
+                                   : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, keep, stream);
     a.n = 0;
     wgs = 0;
     for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
@@ -270,6 +273,48 @@ int gws_sample_bwd(const gws_tensor* t, int n, uint64_t step, void* stream) {
     if (rc != GWS_OK) return rc;
   }
   return run_batched(t, n, nullptr, nullptr, false, 0, step, (hipStream_t)stream);
+}
+
+int gws_sample_fwd_basis(const gws_tensor* t, int n, int basis, int fmt, uint64_t step, void* stream) {
+  if (basis == GWS_BASIS_BITS) return gws_sample_fwd(t, n, fmt, step, stream);
+  if (basis != GWS_BASIS_UNIFORM_BF16 && basis != GWS_BASIS_BOX_MULLER) return GWS_ERR_FORMAT;
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_fwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, false, basis);
+}
+
+int gws_sample_bwd_basis(const gws_tensor* t, int n, int basis, uint64_t step, void* stream) {
+  if (basis == GWS_BASIS_BITS) return gws_sample_bwd(t, n, step, stream);
+  if (basis != GWS_BASIS_UNIFORM_BF16 && basis != GWS_BASIS_BOX_MULLER) return GWS_ERR_FORMAT;
+  if (n < 0) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_bwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  return run_batched(t, n, nullptr, nullptr, false, 0, step, (hipStream_t)stream, false, basis);
+}
+
+int gws_noise_basis(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t col0, uint64_t seed, uint64_t step,
+                    int basis, void* stream) {
+  if (basis != GWS_BASIS_BITS && basis != GWS_BASIS_UNIFORM_BF16 && basis != GWS_BASIS_BOX_MULLER) return GWS_ERR_FORMAT;
+  if (basis == GWS_BASIS_BITS) return GWS_ERR_FORMAT;   // the bit basis has its own, packed dump: gws_noise_packed
+  if (rows < 0 || cols < 0 || row0 < 0 || col0 < 0 || (col0 & 7) != 0 || (cols & 7) != 0) return GWS_ERR_SHAPE;
+  if (rows + row0 > (int64_t)0xFFFFFFFFll || (cols + col0) / 8 > (int64_t)0xFFFFFFFFll) return GWS_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return GWS_OK;
+  if (!out) return GWS_ERR_NULL;
+  if (!aligned(out, 16)) return GWS_ERR_ALIGN;
+  const int64_t ngrp = cols / 8;
+  if ((uint64_t)rows * (uint64_t)ngrp >= ((uint64_t)1 << 39)) return GWS_ERR_SHAPE;
+  return launch_noise_basis(out, (uint32_t)rows, (uint32_t)ngrp, (uint32_t)row0, (uint32_t)(col0 / 8), seed, step, basis,
+                            (hipStream_t)stream);
 }
 
 int gws_copy_tiles(const gws_tensor* t, int n, void* stream) {

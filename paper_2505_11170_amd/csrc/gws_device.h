@@ -339,6 +339,133 @@ __device__ __forceinline__ MxCodes sample_group_mx_fp8(const u32x4 w, const Nois
   return c;
 }
 
+// ---------------------------------------------------------------------------
+// Comparison noise bases (paper Sec. 4): the same pipeline with R drawn as a BF16
+// U(-0.5, 0.5) value (the paper's "DiffQ" extension) or as the exact rounded normal
+// round(N(0,1) / 2) from a Box-Muller transform (the "bm" baseline of its forward
+// unit benchmark).  Both take the group's Philox call as it is; only the map from
+// the 128 bits to the eight R differs.
+//   uniform:    element k owns byte k % 4 of word k / 4; R = (2 byte - 255) / 512, one of the
+//               256 midpoints of a 1/256 grid on (-0.5, 0.5), each a BF16 value.  R * s is not
+//               exact here and is rounded to BF16 before the add (the BF16 operator of Sec. 3.3).
+//   Box-Muller: the pair of elements (2d, 2d + 1) owns word d; u1 = (low half + 0.5) / 2^16,
+//               u2 = (high half + 0.5) / 2^16, z = sqrt(-2 ln u1) (cos, sin)(2 pi u2),
+//               R = rint(z / 2).  Floating point decides an integer here, so the fp32 operations
+//               and their order are fixed (no contraction, correctly rounded square root).
+// ---------------------------------------------------------------------------
+constexpr int kBasisBits = 0, kBasisUniform = 1, kBasisBoxMuller = 2;
+
+// R of elements 2d and 2d + 1 of a group as fp32 (exact), uniform basis.
+template <int D>
+__device__ __forceinline__ void uniform_pair(const Philox4& x, float& r_lo, float& r_hi) {
+  const uint32_t word = (D >> 1) ? x.x1 : x.x0;   // elements 0..3 in x0, 4..7 in x1
+  const float step = __uint_as_float(0x3B800000u), off = __uint_as_float(0xBEFF0000u);   // 2^-8, -255/512
+  r_lo = __fmaf_rn(byte_to_f32<2 * (D & 1)>(word), step, off);
+  r_hi = __fmaf_rn(byte_to_f32<2 * (D & 1) + 1>(word), step, off);
+}
+
+// ln(u) for u = (k + 0.5) / 2^16: u = m 2^e with m in [1/sqrt2, sqrt2), ln u = e ln2 + f P(f), f = m - 1,
+// P of degree 8 evaluated by Horner's rule with fused multiply-adds.
+__device__ __forceinline__ float bm_log(float u) {
+  const uint32_t ub = __float_as_uint(u);
+  int e = (int)(ub >> 23) - 127;
+  float m = __uint_as_float((ub & 0x007FFFFFu) | 0x3F800000u);
+  if (m > __uint_as_float(0x3FB504F3u)) {
+    m = __fmul_rn(m, 0.5f);
+    e += 1;
+  }
+  const float f = __fsub_rn(m, 1.0f);
+  float p = __uint_as_float(0x3DB31375u);
+  p = __fmaf_rn(p, f, __uint_as_float(0xBE13394Fu));
+  p = __fmaf_rn(p, f, __uint_as_float(0x3E191428u));
+  p = __fmaf_rn(p, f, __uint_as_float(0xBE2994DFu));
+  p = __fmaf_rn(p, f, __uint_as_float(0x3E4C5C05u));
+  p = __fmaf_rn(p, f, __uint_as_float(0xBE8002D3u));
+  p = __fmaf_rn(p, f, __uint_as_float(0x3EAAABC8u));
+  p = __fmaf_rn(p, f, __uint_as_float(0xBEFFFFFCu));
+  p = __fmaf_rn(p, f, 1.0f);
+  return __fmaf_rn((float)e, __uint_as_float(0x3F317218u), __fmul_rn(p, f));
+}
+
+// R of the two elements that own `word`, as fp32 in {-2, -1, -0, 0, 1, 2}.
+__device__ __forceinline__ void box_muller_pair(uint32_t word, float& r_lo, float& r_hi) {
+  const float u1 = __fmul_rn(__fadd_rn((float)(word & 0xFFFFu), 0.5f), __uint_as_float(0x37800000u));
+  const float L = __fmul_rn(-2.0f, bm_log(u1));
+  const float r = __builtin_sqrtf(L);   // correctly rounded
+  const uint32_t hi = word >> 16, q = hi >> 14, j = hi & 0x3FFFu;
+  // angle = q pi/2 + pi/4 + t, t = (2 j + 1 - 16384) fl(pi / 65536) in (-pi/4, pi/4)
+  const float t = __fmul_rn((float)(2 * (int)j + 1 - 16384), __uint_as_float(0x38490FDBu));
+  const float t2 = __fmul_rn(t, t);
+  float sp = __uint_as_float(0xB94D6501u);
+  sp = __fmaf_rn(sp, t2, __uint_as_float(0x3C088615u));
+  sp = __fmaf_rn(sp, t2, __uint_as_float(0xBE2AAAA9u));
+  const float st = __fmaf_rn(__fmul_rn(t, t2), sp, t);
+  float cp = __uint_as_float(0x37CD3809u);
+  cp = __fmaf_rn(cp, t2, __uint_as_float(0xBAB60706u));
+  cp = __fmaf_rn(cp, t2, __uint_as_float(0x3D2AAAA6u));
+  cp = __fmaf_rn(cp, t2, __uint_as_float(0xBF000000u));
+  const float ct = __fmaf_rn(t2, cp, 1.0f);
+  const float h = __uint_as_float(0x3F3504F3u);
+  const float c = __fmul_rn(__fsub_rn(ct, st), h), sn = __fmul_rn(__fadd_rn(ct, st), h);
+  // q quarter turns: (c, s) -> (-s, c) -> (-c, -s) -> (s, -c); negation is a sign-bit flip
+  const uint32_t cb = __float_as_uint(c), sb = __float_as_uint(sn);
+  const uint32_t cq = ((q & 1) ? sb : cb) ^ (((q + 1) & 2) << 30);
+  const uint32_t sq = ((q & 1) ? cb : sb) ^ ((q & 2) << 30);
+  r_lo = __builtin_rintf(__fmul_rn(0.5f, __fmul_rn(r, __uint_as_float(cq))));
+  r_hi = __builtin_rintf(__fmul_rn(0.5f, __fmul_rn(r, __uint_as_float(sq))));
+}
+
+// R of elements 2d, 2d + 1 under a comparison basis.
+template <int BASIS, int D>
+__device__ __forceinline__ void basis_pair(const Philox4& x, float& r_lo, float& r_hi) {
+  if (BASIS == kBasisUniform) {
+    uniform_pair<D>(x, r_lo, r_hi);
+  } else {
+    box_muller_pair(D == 0 ? x.x0 : D == 1 ? x.x1 : D == 2 ? x.x2 : x.x3, r_lo, r_hi);
+  }
+}
+
+// bf16_rne(w + PQN) for elements 2d, 2d + 1 under a comparison basis: PQN = bf16_rne(R * s) (exact for the
+// integer R of the Box-Muller basis, where the fused multiply-add gives the same bits in one step).
+template <int BASIS, int D>
+__device__ __forceinline__ uint32_t sampled_pair_basis(uint32_t wd, const Philox4& x, const BlockScale& b) {
+  float r_lo, r_hi;
+  basis_pair<BASIS, D>(x, r_lo, r_hi);
+  const float s = __uint_as_float(b.s_bits);
+  const float w_lo = __uint_as_float(wd << 16), w_hi = __uint_as_float(wd & 0xFFFF0000u);
+  if (BASIS == kBasisUniform) {
+    const uint32_t pq = pack_bf16_rne(__fmul_rn(r_lo, s), __fmul_rn(r_hi, s));
+    return pack_bf16_rne(__fadd_rn(w_lo, __uint_as_float(pq << 16)), __fadd_rn(w_hi, __uint_as_float(pq & 0xFFFF0000u)));
+  }
+  return pack_bf16_rne(__fmaf_rn(r_lo, s, w_lo), __fmaf_rn(r_hi, s, w_hi));
+}
+
+// The eight R of a group under a comparison basis as four packed BF16 pairs (every R is a BF16 value).
+template <int BASIS>
+__device__ __forceinline__ u32x4 basis_group_bf16(const Philox4& x) {
+  float lo[4], hi[4];
+  basis_pair<BASIS, 0>(x, lo[0], hi[0]);
+  basis_pair<BASIS, 1>(x, lo[1], hi[1]);
+  basis_pair<BASIS, 2>(x, lo[2], hi[2]);
+  basis_pair<BASIS, 3>(x, lo[3], hi[3]);
+  return u32x4{pack_bf16_rne(lo[0], hi[0]), pack_bf16_rne(lo[1], hi[1]), pack_bf16_rne(lo[2], hi[2]), pack_bf16_rne(lo[3], hi[3])};
+}
+
+// sum over one group of g .* R under a comparison basis (products exact, fp32 accumulation, fixed order).
+template <int BASIS>
+__device__ __forceinline__ float dot_group_basis(const u32x4 g, const Philox4& x, float acc) {
+  const u32x4 r = basis_group_bf16<BASIS>(x);
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t gd = g[d], rd = r[d];
+    bf16x2 gv, rv;
+    __builtin_memcpy(&gv, &gd, 4);
+    __builtin_memcpy(&rv, &rd, 4);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(gv, rv, acc, false);
+  }
+  return acc;
+}
+
 // sum over one group of g .* (2R), two elements per v_dot2 (products exact, fp32
 // accumulation).  2R in {0, +-2, +-4} has the BF16 patterns sign<<15 | nz<<14 |
 // m2<<7.  The three bits of every element are first moved to the top of a byte

@@ -56,6 +56,11 @@ static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the siz
 
 int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream);
 int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
+// the same two passes with R drawn from a comparison basis (kBasisUniform, kBasisBoxMuller)
+int launch_sample_fwd_basis(const LaunchArgs& a, uint32_t n_wg, int fmt, bool keep, int basis, hipStream_t stream);
+int launch_sample_bwd_basis(const LaunchArgs& a, uint32_t n_wg, int basis, hipStream_t stream);
+int launch_noise_basis(void* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0, uint64_t seed, uint64_t step,
+                       int basis, hipStream_t stream);
 int launch_copy_tiles(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_block_absmax(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
 int launch_noise_packed(uint32_t* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0,

@@ -107,18 +107,19 @@ __device__ __forceinline__ void walk_tiles(const LaunchArgs& a, const TileDesc& 
 // MX: write element codes and E8M0 block scales instead of the BF16 container.
 // STREAM: non-temporal stores of w_hat (right when it is not read again soon); false keeps w_hat in
 // the caches for a GEMM that follows immediately.
-template <int FMT, bool MX = false, bool STREAM = true>
+// BASIS: the method's bit-built noise, or one of the two comparison bases.
+template <int FMT, bool MX = false, bool STREAM = true, int BASIS = kBasisBits>
 __global__ __launch_bounds__(kThreads) void sample_fwd_kernel(const LaunchArgs a) {
   uint32_t byg, bxg;
   const TileDesc d = locate(a, byg, bxg);
   const uint32_t lane = threadIdx.x & 63;
   walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
-    if (t.full) fwd_tile<FMT, true, STREAM, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
-    else fwd_tile<FMT, false, STREAM, MX>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    if (t.full) fwd_tile<FMT, true, STREAM, MX, false, BASIS>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
+    else fwd_tile<FMT, false, STREAM, MX, false, BASIS>(a.step_lo, a.step_hi, d, t, by, col_base, lane);
   });
 }
 
-template <bool FULL, bool COPY>
+template <bool FULL, bool COPY, int BASIS = kBasisBits>
 __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d, const Tile& t, uint32_t by,
                                          uint32_t col_base, uint32_t lane) {
   const uint32_t row_base = by * 32;
@@ -154,11 +155,16 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
       if (FULL || t.nv[i] == 8) store16(dst, t.v[i]);
       else store_partial(dst, t.v[i], t.nv[i]);
     }
-    const Noise n = group_noise(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
     const u32x4 gv = (FULL || t.nv[i] == 8) ? t.v[i] : mask_group(t.v[i], t.nv[i]);
-    acc = dot_group_2r(gv, n, acc);
+    if constexpr (BASIS == kBasisBits) {
+      const Noise n = group_noise(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
+      acc = dot_group_2r(gv, n, acc);
+    } else {
+      const Philox4 x = philox4x32_10(cg, d.row0 + row, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
+      acc = dot_group_basis<BASIS>(gv, x, acc);
+    }
   }
-  acc = block_sum_f32(acc) * 0.5f;
+  acc = block_sum_f32(acc) * (BASIS == kBasisBits ? 0.5f : 1.0f);
 
   if (writer) {
     const float neg_ln2 = __uint_as_float(0xBF317218u);  // -ln 2
@@ -174,6 +180,7 @@ __device__ __forceinline__ void bwd_tile(const LaunchArgs& a, const TileDesc& d,
   }
 }
 
+template <int BASIS = kBasisBits>
 __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a) {
   uint32_t byg, bxg;
   const TileDesc d = locate(a, byg, bxg);
@@ -181,11 +188,11 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a
   const bool copy = d.p1 != nullptr;  // NULL: the pass-through is an alias
   walk_tiles(a, d, byg, bxg, [&](uint32_t by, uint32_t col_base, Tile& t) {
     if (t.full) {
-      if (copy) bwd_tile<true, true>(a, d, t, by, col_base, lane);
-      else bwd_tile<true, false>(a, d, t, by, col_base, lane);
+      if (copy) bwd_tile<true, true, BASIS>(a, d, t, by, col_base, lane);
+      else bwd_tile<true, false, BASIS>(a, d, t, by, col_base, lane);
     } else {
-      if (copy) bwd_tile<false, true>(a, d, t, by, col_base, lane);
-      else bwd_tile<false, false>(a, d, t, by, col_base, lane);
+      if (copy) bwd_tile<false, true, BASIS>(a, d, t, by, col_base, lane);
+      else bwd_tile<false, false, BASIS>(a, d, t, by, col_base, lane);
     }
   });
 }
@@ -240,9 +247,69 @@ __global__ __launch_bounds__(256) void noise_packed_kernel(uint32_t* __restrict_
   out[idx] = packed_codes(group_noise(cg0 + cgl, row0 + row, step_lo, step_hi, seed_lo, seed_hi));
 }
 
+// R of every element under a comparison basis, as BF16 values [rows x 8 ngrp]: one thread per group of 8.
+template <int BASIS>
+__global__ __launch_bounds__(256) void noise_basis_kernel(u32x4* __restrict__ out, uint32_t rows, uint32_t ngrp,
+                                                          uint32_t row0, uint32_t cg0, uint32_t seed_lo, uint32_t seed_hi,
+                                                          uint32_t step_lo, uint32_t step_hi) {
+  const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (uint64_t)rows * ngrp) return;
+  const uint32_t row = (uint32_t)(idx / ngrp), cgl = (uint32_t)(idx % ngrp);
+  out[idx] = basis_group_bf16<BASIS>(philox4x32_10(cg0 + cgl, row0 + row, step_lo, step_hi, seed_lo, seed_hi));
+}
+
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
+template <int BASIS>
+static int launch_fwd_basis(const LaunchArgs& a, uint32_t n_wg, int fmt, bool keep, hipStream_t stream) {
+  if (keep) {
+    switch (fmt) {
+      case GWS_FMT_BF16: hipLaunchKernelGGL((sample_fwd_kernel<0, false, false, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, false, false, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, false, false, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      default: return GWS_ERR_FORMAT;
+    }
+  } else {
+    switch (fmt) {
+      case GWS_FMT_BF16: hipLaunchKernelGGL((sample_fwd_kernel<0, false, true, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, false, true, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, false, true, BASIS>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
+      default: return GWS_ERR_FORMAT;
+    }
+  }
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+int launch_sample_fwd_basis(const LaunchArgs& a, uint32_t n_wg, int fmt, bool keep, int basis, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
+  if (basis == kBasisUniform) return launch_fwd_basis<kBasisUniform>(a, n_wg, fmt, keep, stream);
+  if (basis == kBasisBoxMuller) return launch_fwd_basis<kBasisBoxMuller>(a, n_wg, fmt, keep, stream);
+  return GWS_ERR_FORMAT;
+}
+
+int launch_sample_bwd_basis(const LaunchArgs& a, uint32_t n_wg, int basis, hipStream_t stream) {
+  if (n_wg == 0) return GWS_OK;
+  if (basis == kBasisUniform) hipLaunchKernelGGL(sample_bwd_kernel<kBasisUniform>, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  else if (basis == kBasisBoxMuller) hipLaunchKernelGGL(sample_bwd_kernel<kBasisBoxMuller>, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  else return GWS_ERR_FORMAT;
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
+int launch_noise_basis(void* out, uint32_t rows, uint32_t ngrp, uint32_t row0, uint32_t cg0, uint64_t seed, uint64_t step,
+                       int basis, hipStream_t stream) {
+  const uint64_t total = (uint64_t)rows * ngrp;
+  if (total == 0) return GWS_OK;
+  const uint32_t grid = (uint32_t)((total + 255) / 256);
+  const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32), tlo = (uint32_t)step, thi = (uint32_t)(step >> 32);
+  if (basis == kBasisUniform)
+    hipLaunchKernelGGL(noise_basis_kernel<kBasisUniform>, dim3(grid), dim3(256), 0, stream, (u32x4*)out, rows, ngrp, row0, cg0, slo, shi, tlo, thi);
+  else if (basis == kBasisBoxMuller)
+    hipLaunchKernelGGL(noise_basis_kernel<kBasisBoxMuller>, dim3(grid), dim3(256), 0, stream, (u32x4*)out, rows, ngrp, row0, cg0, slo, shi, tlo, thi);
+  else return GWS_ERR_FORMAT;
+  return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
+}
+
 int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
   if (keep && !mx) {
@@ -285,7 +352,7 @@ int launch_block_absmax(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) 
 
 int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
-  hipLaunchKernelGGL(sample_bwd_kernel, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  hipLaunchKernelGGL(sample_bwd_kernel<kBasisBits>, dim3(n_wg), dim3(kThreads), 0, stream, a);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 

@@ -106,7 +106,8 @@ __device__ __forceinline__ void store_codes(GWS_GLOBAL uint8_t* row, uint32_t co
 // instead of the BF16 container.
 // BT_PRE: the caller has already fetched this lane's block parameter (bt_pre), as a wavefront that works
 // through several tiles alone does together with the tile loads, so that its latency is not paid per tile.
-template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false>
+// BASIS: kBasisBits is the method's noise (Sec. 3.4); the other two are the comparison bases (no MX form).
+template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false, int BASIS = kBasisBits>
 __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
                                          uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f) {
   const uint32_t row_base = by * 32;
@@ -149,18 +150,40 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
 
   // ---- noise, add, round, cast, store ----
   const uint32_t cg = d.cg0 + (col >> 3);
+  static_assert(BASIS == kBasisBits || !MX, "the comparison bases have no MX output");
+  // the four BF16 sums of one group (before the cast), whatever the basis
+  auto sampled_group = [&](const u32x4 w, uint32_t row, uint32_t (&pk)[4]) {
+    if constexpr (BASIS == kBasisBits) {
+      const Noise n = group_noise(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const GroupMagnitudes g = group_magnitudes(n);
+      pk[0] = sampled_pair<0>(w[0], g, n, b);
+      pk[1] = sampled_pair<1>(w[1], g, n, b);
+      pk[2] = sampled_pair<2>(w[2], g, n, b);
+      pk[3] = sampled_pair<3>(w[3], g, n, b);
+    } else {
+      const Philox4 x = philox4x32_10(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      pk[0] = sampled_pair_basis<BASIS, 0>(w[0], x, b);
+      pk[1] = sampled_pair_basis<BASIS, 1>(w[1], x, b);
+      pk[2] = sampled_pair_basis<BASIS, 2>(w[2], x, b);
+      pk[3] = sampled_pair_basis<BASIS, 3>(w[3], x, b);
+    }
+  };
   auto finish = [&](bool use_hw) {
     if constexpr (FMT != 2) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (!FULL && t.nv[i] == 0) continue;
         const uint32_t row = row_base + r0 + 8 * i;
-        const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
         if constexpr (MX) {
+          const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
           const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, use_hw);
           store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
         } else {
-          const u32x4 o = sample_group<FMT>(t.v[i], n, b, use_hw);
+          uint32_t pk[4];
+          sampled_group(t.v[i], d.row0 + row, pk);
+          i16x2 chain = {0, 0};
+          const u32x4 o = {cast_pair<FMT>(pk[0], b, use_hw, chain), cast_pair<FMT>(pk[1], b, use_hw, chain),
+                           cast_pair<FMT>(pk[2], b, use_hw, chain), cast_pair<FMT>(pk[3], b, use_hw, chain)};
           GWS_GLOBAL uint16_t* dst = w_hat + (size_t)row * d.ld + col;
           if (FULL || t.nv[i] == 8) {
             if (STREAM) store16(dst, o);
@@ -186,12 +209,12 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         pk[4 * i] = pk[4 * i + 1] = pk[4 * i + 2] = pk[4 * i + 3] = 0;
         continue;
       }
-      const Noise n = group_noise(cg, d.row0 + row_base + r0 + 8 * i, step_lo, step_hi, d.seed_lo, d.seed_hi);
-      const GroupMagnitudes g = group_magnitudes(n);
-      pk[4 * i] = sampled_pair<0>(t.v[i][0], g, n, b);
-      pk[4 * i + 1] = sampled_pair<1>(t.v[i][1], g, n, b);
-      pk[4 * i + 2] = sampled_pair<2>(t.v[i][2], g, n, b);
-      pk[4 * i + 3] = sampled_pair<3>(t.v[i][3], g, n, b);
+      uint32_t p4[4];
+      sampled_group(t.v[i], d.row0 + row_base + r0 + 8 * i, p4);
+      pk[4 * i] = p4[0];
+      pk[4 * i + 1] = p4[1];
+      pk[4 * i + 2] = p4[2];
+      pk[4 * i + 3] = p4[3];
     }
     bf16x32 v;
     __builtin_memcpy(&v, pk, 64);
