@@ -27,6 +27,16 @@ int gws_copy_tiles(const gws_tensor* t, int n, void* stream);
  * system sets for the backward pass.  Uses fields w, scale, rows, cols, ld.                 */
 int gws_block_absmax(const gws_tensor* t, int n, void* stream);
 
+/* gws_sample_bwd with the launch shape chosen by the caller, to measure the choices the library makes:
+ *   variant  -1 = the library's choice; 0 = the kernel for any shape; 1 = the whole-tile kernel (used only
+ *            where every tensor of a launch has rows % 32 == 0, cols % 256 == 0 and an aliased dL/dw)
+ *   per_x    column tiles (256 columns) one workgroup walks; 0 = the library's choice
+ * Same results as gws_sample_bwd whatever the choice.                                                  */
+int gws_sample_bwd_tuned(const gws_tensor* t, int n, uint64_t step, int variant, int per_x, void* stream);
+
+/* The same for gws_sample_fwd: variant -1 / 0 / 1 (whole-tile kernel), per_x as above.               */
+int gws_sample_fwd_tuned(const gws_tensor* t, int n, int fmt, uint64_t step, int variant, int per_x, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

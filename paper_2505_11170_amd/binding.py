@@ -23,7 +23,7 @@ EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_
            "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
            "gws_sample_fwd_basis", "gws_sample_bwd_basis", "gws_noise_basis",
            "gws_derive_seed", "gws_status_string", "gws_version")
-BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax")
+BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax", "gws_sample_bwd_tuned", "gws_sample_fwd_tuned")
 
 
 class GwsError(RuntimeError):
@@ -128,6 +128,10 @@ def load_library() -> ctypes.CDLL:
     L.gws_gemm_bf16_sample_next.restype = ci
     L.gws_copy_tiles.argtypes = [tp, ci, vp]
     L.gws_copy_tiles.restype = ci
+    L.gws_sample_fwd_tuned.argtypes = [tp, ci, ci, u64, ci, ci, vp]
+    L.gws_sample_fwd_tuned.restype = ci
+    L.gws_sample_bwd_tuned.argtypes = [tp, ci, u64, ci, ci, vp]
+    L.gws_sample_bwd_tuned.restype = ci
     L.gws_block_absmax.argtypes = [tp, ci, vp]
     L.gws_block_absmax.restype = ci
     L.gws_linear_bwd_w.argtypes = [vp, vp, i64, i64, i64, tp, ci, u64, vp]
@@ -369,6 +373,20 @@ def gws_copy_tiles(t: Sequence[TensorDesc], stream=None) -> None:
     L = load_library()
     arr, n = _as_c(t)
     _check(L.gws_copy_tiles(arr, n, _stream(stream)), "gws_copy_tiles")
+
+
+def gws_sample_bwd_tuned(t: Sequence[TensorDesc], step: int, variant: int = -1, per_x: int = 0, stream=None) -> None:
+    """``gws_sample_bwd`` with the kernel variant and the column tiles per workgroup chosen by the caller (a measurement aid)."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_bwd_tuned(arr, n, int(step), int(variant), int(per_x), _stream(stream)), "gws_sample_bwd_tuned")
+
+
+def gws_sample_fwd_tuned(t: Sequence[TensorDesc], fmt: int, step: int, variant: int = -1, per_x: int = 0, stream=None) -> None:
+    """``gws_sample_fwd`` with the kernel variant and the column tiles per workgroup chosen by the caller (a measurement aid)."""
+    L = load_library()
+    arr, n = _as_c(t)
+    _check(L.gws_sample_fwd_tuned(arr, n, int(fmt), int(step), int(variant), int(per_x), _stream(stream)), "gws_sample_fwd_tuned")
 
 
 def gws_block_absmax(t: Sequence[TensorDesc], stream=None) -> None:

@@ -112,20 +112,30 @@ constexpr int kAbsmaxOnly = -2;  // the backward launch shape, block-maximum ker
 // 2^31 grid limit allow.  `fwd` selects which pointers a descriptor carries.
 // `bw` (one per tensor) switches on the parametrised bitwidth of Eq. 11 / Eq. 12.
 // `mx` (one per tensor, forward only) switches the output to MX element codes and block scales.
+// Launch-shape choices of a sampling pass; the defaults (-1, 0) let run_batched decide.
+struct Tuning {
+  int variant = -1;   // launch_sample_fwd's / launch_sample_bwd's variant; above 0 only where every tensor qualifies
+  int per_x = 0;      // column tiles per workgroup
+};
+
 // `basis` other than kBasisBits runs the sampling passes on a comparison noise basis (no bw, no mx then).
 int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx_out* mx, bool fwd, int fmt,
-                uint64_t step, hipStream_t stream, bool keep = false, int basis = kBasisBits) {
-  // Tiles per workgroup.  Forward: one (most workgroups, fewest registers; measured best).
-  // Backward does less per tile, so the per-wavefront set-up shows: a workgroup takes up to
-  // four neighbouring column tiles while at least ~3000 workgroups (12 per compute unit)
-  // remain.  Neighbouring column tiles, not rows: the workgroups in flight then still cover
-  // a contiguous stretch of memory, which the memory system rewards.
+                uint64_t step, hipStream_t stream, bool keep = false, int basis = kBasisBits,
+                Tuning tune = Tuning()) {
+  // Tiles per workgroup.  Forward: one (most workgroups; measured best: 2 costs 1-10 %, 4 costs 6-10 %).
+  // Backward does less per tile, so the per-wavefront set-up shows, and its Philox rounds that depend on
+  // the row alone are reused across column tiles: a workgroup takes up to four neighbouring column tiles
+  // while at least ~3000 workgroups (12 per compute unit) remain (measured: 3 best on the 85 M parameters
+  // of GPT2-124M, 4 on the 1B model; 6 and more lose).  Neighbouring column tiles, not rows: the
+  // workgroups in flight then still cover a contiguous stretch of memory, which the memory system rewards.
   uint64_t total = 0;
   for (int i = 0; i < n; ++i)
     if (t[i].rows > 0 && t[i].cols > 0) total += wg_count(t[i], 1, 1);
   uint32_t per_wg = 1, per_x = 1;
-  if (!fwd)
+  if (!fwd) {
     while (per_x < 4 && total / (per_x + 1) >= 3000) ++per_x;
+  }
+  if (tune.per_x > 0) per_x = (uint32_t)tune.per_x;
   // Forward stores: a call that writes little (one weight, a few layers) is usually followed by its
   // consumer, and the whole of w_hat fits in the last-level cache, so it is written with ordinary
   // stores; a call over a model's worth of weights streams past the caches (non-temporal stores).
@@ -140,16 +150,19 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
   a.tiles_per_wg_x = per_x;
   for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
   uint64_t wgs = 0;
+  bool whole_tiles = true;   // every tensor of the pending launch: rows % 32 == 0, cols % 256 == 0, nothing to copy
   auto flush = [&]() -> int {
     if (a.n == 0) return GWS_OK;
+    const int variant = !whole_tiles ? 0 : tune.variant >= 0 ? tune.variant : 1;
     int rc = (!fwd && fmt == kAbsmaxOnly) ? launch_block_absmax(a, (uint32_t)wgs, stream)
              : (!fwd && basis != kBasisBits) ? launch_sample_bwd_basis(a, (uint32_t)wgs, basis, stream)
-             : !fwd ? launch_sample_bwd(a, (uint32_t)wgs, stream)
+             : !fwd ? launch_sample_bwd(a, (uint32_t)wgs, variant, stream)
              : fmt == kCopyOnly ? launch_copy_tiles(a, (uint32_t)wgs, stream)
              : basis != kBasisBits ? launch_sample_fwd_basis(a, (uint32_t)wgs, fmt, keep, basis, stream)
-                                   : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, keep, stream);
+                                   : launch_sample_fwd(a, (uint32_t)wgs, fmt, mx != nullptr, keep, variant, stream);
     a.n = 0;
     wgs = 0;
+    whole_tiles = true;
     for (int i = 0; i < kMaxTensorsPerLaunch; ++i) a.tile_begin[i] = 0x7FFFFFFFu;
     return rc;
   };
@@ -166,10 +179,12 @@ int run_batched(const gws_tensor* t, int n, const gws_bitwidth* bw, const gws_mx
     d.first_wg = (uint32_t)wgs;
     if (fwd) {
       d.p0 = t[i].w; d.p1 = t[i].w_hat; d.p2 = (void*)t[i].bt; d.p3 = t[i].scale;
+      if ((t[i].rows & 31) != 0 || (t[i].cols & (kTileCols - 1)) != 0) whole_tiles = false;
     } else if (fmt == kAbsmaxOnly) {
       d.p0 = t[i].w; d.p1 = nullptr; d.p2 = nullptr; d.p3 = t[i].scale;
     } else {
       d.p0 = t[i].g; d.p1 = (t[i].dw == t[i].g) ? nullptr : t[i].dw; d.p2 = t[i].dbt; d.p3 = t[i].scale;
+      if (d.p1 != nullptr || (t[i].rows & 31) != 0 || (t[i].cols & (kTileCols - 1)) != 0) whole_tiles = false;
     }
     fill_common(d, t[i], per_x);
     d.p4 = nullptr;
@@ -315,6 +330,35 @@ int gws_noise_basis(void* out, int64_t rows, int64_t cols, int64_t row0, int64_t
   if ((uint64_t)rows * (uint64_t)ngrp >= ((uint64_t)1 << 39)) return GWS_ERR_SHAPE;
   return launch_noise_basis(out, (uint32_t)rows, (uint32_t)ngrp, (uint32_t)row0, (uint32_t)(col0 / 8), seed, step, basis,
                             (hipStream_t)stream);
+}
+
+int gws_sample_bwd_tuned(const gws_tensor* t, int n, uint64_t step, int variant, int per_x, void* stream) {
+  if (n < 0 || variant < -1 || variant > 1 || per_x < 0 || per_x > 64) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_bwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  Tuning tune;
+  tune.variant = variant;
+  tune.per_x = per_x;
+  return run_batched(t, n, nullptr, nullptr, false, 0, step, (hipStream_t)stream, false, kBasisBits, tune);
+}
+
+int gws_sample_fwd_tuned(const gws_tensor* t, int n, int fmt, uint64_t step, int variant, int per_x, void* stream) {
+  if (n < 0 || variant < -1 || variant > 1 || per_x < 0 || per_x > 64) return GWS_ERR_SHAPE;
+  if (n == 0) return GWS_OK;
+  if (!t) return GWS_ERR_NULL;
+  if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
+  for (int i = 0; i < n; ++i) {
+    int rc = check_fwd(t[i]);
+    if (rc != GWS_OK) return rc;
+  }
+  Tuning tune;
+  tune.variant = variant;
+  tune.per_x = per_x;
+  return run_batched(t, n, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, false, kBasisBits, tune);
 }
 
 int gws_copy_tiles(const gws_tensor* t, int n, void* stream) {

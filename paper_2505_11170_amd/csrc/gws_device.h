@@ -54,6 +54,61 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
   return Philox4{c0, c1, c2, c3};
 }
 
+// The four Philox calls of a lane (rows row[0..3], one column group) with the work of the first three rounds
+// that does not depend on all of the counter done once.  With counter (cg, row, step_lo, step_hi):
+//   round 0: M1 * step_lo is uniform; M0 * cg depends on the column group only; the new c0 on the row only;
+//   round 1: M0 * c0 depends on the row only (PhiloxRows: kept across the column tiles a wavefront walks),
+//            M1 * c2 on the column group only;
+//   round 2: M0 * c0 depends on the column group only; from M1 * c2 on everything depends on both.
+// 63 multiplies per four calls instead of 80 (67 with the row part), same bits as philox4x32_10.
+struct PhiloxRows {
+  uint32_t hi[4], lo[4];   // M0 * (c0 after round 0) for the four rows
+};
+
+__device__ __forceinline__ PhiloxRows philox_rows(const uint32_t (&row)[4], uint32_t step_lo, uint32_t k0) {
+  const uint32_t base = (uint32_t)(((uint64_t)0xCD9E8D57u * step_lo) >> 32) ^ k0;   // uniform
+  PhiloxRows r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint64_t d = (uint64_t)0xD2511F53u * (base ^ row[i]);
+    r.hi[i] = (uint32_t)(d >> 32);
+    r.lo[i] = (uint32_t)d;
+  }
+  return r;
+}
+
+__device__ __forceinline__ void philox_four_rows(uint32_t cg, const PhiloxRows& rp, uint32_t step_lo, uint32_t step_hi,
+                                                 uint32_t k0, uint32_t k1, Philox4 (&out)[4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  const uint32_t c1_1 = (uint32_t)((uint64_t)M1 * step_lo);                      // round 0, uniform
+  const uint64_t b = (uint64_t)M0 * cg;                                          // round 0, column group
+  const uint32_t c2_1 = xor3((uint32_t)(b >> 32), step_hi, k1), c3_1 = (uint32_t)b;
+  const uint64_t c = (uint64_t)M1 * c2_1;                                        // round 1, column group
+  const uint32_t c0_2 = xor3((uint32_t)(c >> 32), c1_1, k0 + W0), c1_2 = (uint32_t)c;
+  const uint64_t f = (uint64_t)M0 * c0_2;                                        // round 2, column group
+  const uint32_t hi_f = (uint32_t)(f >> 32), c3_3 = (uint32_t)f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t c2_2 = xor3(rp.hi[i], c3_1, k1 + W1), c3_2 = rp.lo[i];        // round 1, row part joins
+    const uint64_t e = (uint64_t)M1 * c2_2;                                      // round 2
+    uint32_t c0 = xor3((uint32_t)(e >> 32), c1_2, k0 + 2 * W0), c1 = (uint32_t)e;
+    uint32_t c2 = xor3(hi_f, c3_2, k1 + 2 * W1), c3 = c3_3;
+    uint32_t ka = k0 + 3 * W0, kb = k1 + 3 * W1;
+#pragma unroll
+    for (int r = 3; r < 10; ++r) {
+      const uint64_t p0 = (uint64_t)M0 * c0, p1 = (uint64_t)M1 * c2;
+      const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, ka), n2 = xor3((uint32_t)(p0 >> 32), c3, kb);
+      c1 = (uint32_t)p1;
+      c3 = (uint32_t)p0;
+      c0 = n0;
+      c2 = n2;
+      ka += W0;
+      kb += W1;
+    }
+    out[i] = Philox4{c0, c1, c2, c3};
+  }
+}
+
 // ---------------------------------------------------------------------------
 // 128 random bits -> the noise of eight elements (paper Sec. 3.4, Eq. 9 and
 // Eq. 10), evaluated for all eight at once on nibble planes.  Each element owns

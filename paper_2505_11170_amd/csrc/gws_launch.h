@@ -54,8 +54,10 @@ struct LaunchArgs {
 };
 static_assert(sizeof(LaunchArgs) <= 6144, "kernel arguments: keep within the size verified on the device");
 
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream);
-int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream);
+// variant: 0 = any shape (sample_fwd_kernel); 1 = whole tiles only (sample_fwd_full_kernel)
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, int variant, hipStream_t stream);
+// variant: 0 = any shape (sample_bwd_kernel); 1 = whole tiles and aliased dL/dw only (sample_bwd_full_kernel)
+int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, int variant, hipStream_t stream);
 // the same two passes with R drawn from a comparison basis (kBasisUniform, kBasisBoxMuller)
 int launch_sample_fwd_basis(const LaunchArgs& a, uint32_t n_wg, int fmt, bool keep, int basis, hipStream_t stream);
 int launch_sample_bwd_basis(const LaunchArgs& a, uint32_t n_wg, int basis, hipStream_t stream);

@@ -197,6 +197,94 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_kernel(const LaunchArgs a
   });
 }
 
+// The forward pass for tensors of whole tiles only (rows a multiple of 32, columns of 256): a workgroup walks
+// `tiles_per_wg_x` neighbouring column tiles of one block row, straight-line per tile, and keeps the row-only
+// share of its Philox calls across them.
+template <int FMT, bool MX, bool STREAM>
+__global__ __launch_bounds__(kThreads) void sample_fwd_full_kernel(const LaunchArgs a) {
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const GWS_GLOBAL uint16_t* __restrict__ src = global_ptr<uint16_t>(d.p0);
+  const uint32_t ntx = d.cols / kTileCols;
+  const uint32_t bx0 = bxg * a.tiles_per_wg_x, bx_end = min(bx0 + a.tiles_per_wg_x, ntx);
+  uint32_t rows[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) rows[i] = d.row0 + byg * 32 + r0 + 8 * i;
+  const PhiloxRows rp = philox_rows(rows, a.step_lo, d.seed_lo);
+  for (uint32_t bx = bx0; bx < bx_end; ++bx) {
+    const uint32_t col_base = bx * kTileCols + wave * 64;
+    Tile t = load_tile(src, d, byg, col_base, col_base + gc * 8, r0);   // always a whole tile here
+    fwd_tile<FMT, true, STREAM, MX>(a.step_lo, a.step_hi, d, t, byg, col_base, lane, 0.0f, &rp);
+  }
+}
+
+// The backward pass for the shape the method meets in a model: every tensor of the launch has whole tiles only
+// (rows a multiple of 32, columns of 256) and dL/dw is an alias (nothing to copy).  Straight-line per tile, and
+// the vector ALU work is cut where it can be: the Philox rounds that depend on the row alone are computed once
+// per wavefront and reused for every column tile it walks, those that depend on the column group alone once per
+// tile (288 vector instructions per tile against about 330 in the kernel for any shape).  The next tile's loads
+// are issued after the current tile's arithmetic and complete under the next tile's Philox rounds; issuing them
+// a whole tile ahead was measured slower (16 more registers cost a wavefront of occupancy).
+__global__ __launch_bounds__(kThreads) void sample_bwd_full_kernel(const LaunchArgs a) {
+  uint32_t byg, bxg;
+  const TileDesc d = locate(a, byg, bxg);
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const GWS_GLOBAL uint16_t* __restrict__ src = global_ptr<uint16_t>(d.p0);
+  GWS_GLOBAL float* __restrict__ dbt = global_ptr<float>(d.p2);
+  const GWS_GLOBAL float* __restrict__ scale = global_ptr<float>(d.p3);
+  const uint32_t ntx = d.cols / kTileCols, nbc = d.cols >> 5;
+  const uint32_t by = byg;                                                  // one block row per workgroup
+  const uint32_t bx0 = bxg * a.tiles_per_wg_x, bx_end = min(bx0 + a.tiles_per_wg_x, ntx);
+  const uint32_t row_base = by * 32;
+  const bool writer = (gc & 3) == 0 && r0 == 0;
+
+  uint32_t rows[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) rows[i] = d.row0 + row_base + r0 + 8 * i;
+  const PhiloxRows rp = philox_rows(rows, a.step_lo, d.seed_lo);
+
+  const GWS_GLOBAL uint16_t* row_ptr = src + (size_t)(row_base + r0) * d.ld + wave * 64 + gc * 8;
+  const size_t row_step = (size_t)8 * d.ld;
+  u32x4 v[4];
+  float s32 = 0.0f, bi = 0.0f;
+  auto load4 = [&](uint32_t bx) {
+    const GWS_GLOBAL uint16_t* p = row_ptr + (size_t)bx * kTileCols;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = load16(p + i * row_step);
+    if (writer) {   // the block's writer lane fetches what it needs with the tile
+      const size_t blk = (size_t)by * nbc + ((bx * kTileCols + wave * 64) >> 5) + (gc >> 2);
+      s32 = scale[blk];
+      if (d.p4 != nullptr) bi = global_ptr<float>(d.p4)[blk];
+    }
+  };
+  load4(bx0);
+  for (uint32_t bx = bx0; bx < bx_end; ++bx) {
+    const uint32_t col = bx * kTileCols + wave * 64 + gc * 8;
+    Philox4 x[4];
+    philox_four_rows(d.cg0 + (col >> 3), rp, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi, x);
+    // sum_{b_l}(g .* R) as sum(g .* 2R) / 2: exact products, fixed order (see bwd_tile)
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = dot_group_2r(v[i], noise_planes(x[i]), acc);
+    acc = block_sum_f32(acc) * 0.5f;
+    if (writer) {
+      const size_t blk = (size_t)by * nbc + (col >> 5);
+      const float neg_ln2 = __uint_as_float(0xBF317218u);   // -ln 2
+      float grad = (neg_ln2 * s32) * acc;                   // dL/db_t, Eq. 4
+      if (d.p4 != nullptr) {                                // dL'/db_i, Eq. 11 and Eq. 12 (as in bwd_tile)
+        const float btv = __fadd_rn(d.b_target, __fmul_rn(bi, d.b_delta));
+        const float sgn = btv > d.b_target ? 1.0f : (btv < d.b_target ? -1.0f : 0.0f);
+        grad = d.b_delta * (grad + d.lambda_m * sgn);
+      }
+      dbt[blk] = grad;
+    }
+    if (bx + 1 < bx_end) load4(bx + 1);
+  }
+}
+
 // The forward kernel's memory traffic without its arithmetic: every tile is loaded and
 // stored back unchanged, same workgroup shape, same loads and stores.  What this kernel
 // reaches is the ceiling the memory system sets for the access pattern.
@@ -310,33 +398,39 @@ int launch_noise_basis(void* out, uint32_t rows, uint32_t ngrp, uint32_t row0, u
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
-int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, hipStream_t stream) {
+#define GWS_FWD_CASES(KERNEL)                                                                                             \
+  if (mx) {                                                                                                               \
+    switch (fmt) {                                                                                                        \
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((KERNEL<1, true, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;  \
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((KERNEL<2, true, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;  \
+      default: return GWS_ERR_FORMAT;                                                                                     \
+    }                                                                                                                     \
+  } else if (keep) {                                                                                                      \
+    switch (fmt) {                                                                                                        \
+      case GWS_FMT_BF16: hipLaunchKernelGGL((KERNEL<0, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;    \
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((KERNEL<1, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break; \
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((KERNEL<2, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break; \
+      default: return GWS_ERR_FORMAT;                                                                                     \
+    }                                                                                                                     \
+  } else {                                                                                                                \
+    switch (fmt) {                                                                                                        \
+      case GWS_FMT_BF16: hipLaunchKernelGGL((KERNEL<0, false, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;     \
+      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((KERNEL<1, false, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;  \
+      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((KERNEL<2, false, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;  \
+      default: return GWS_ERR_FORMAT;                                                                                     \
+    }                                                                                                                     \
+  }
+
+int launch_sample_fwd(const LaunchArgs& a, uint32_t n_wg, int fmt, bool mx, bool keep, int variant, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
-  if (keep && !mx) {
-    switch (fmt) {
-      case GWS_FMT_BF16: hipLaunchKernelGGL((sample_fwd_kernel<0, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, false, false>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-      default: return GWS_ERR_FORMAT;
-    }
-    return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
-  }
-  if (mx) {
-    switch (fmt) {
-      case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL((sample_fwd_kernel<1, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-      case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL((sample_fwd_kernel<2, true>), dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-      default: return GWS_ERR_FORMAT;
-    }
-    return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
-  }
-  switch (fmt) {
-    case GWS_FMT_BF16: hipLaunchKernelGGL(sample_fwd_kernel<0>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-    case GWS_FMT_FP8_E4M3: hipLaunchKernelGGL(sample_fwd_kernel<1>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-    case GWS_FMT_FP6_E3M2: hipLaunchKernelGGL(sample_fwd_kernel<2>, dim3(n_wg), dim3(kThreads), 0, stream, a); break;
-    default: return GWS_ERR_FORMAT;
+  if (variant == 1) {
+    GWS_FWD_CASES(sample_fwd_full_kernel)
+  } else {
+    GWS_FWD_CASES(sample_fwd_kernel)
   }
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
+#undef GWS_FWD_CASES
 
 int launch_copy_tiles(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
@@ -350,9 +444,10 @@ int launch_block_absmax(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) 
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 
-int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, hipStream_t stream) {
+int launch_sample_bwd(const LaunchArgs& a, uint32_t n_wg, int variant, hipStream_t stream) {
   if (n_wg == 0) return GWS_OK;
-  hipLaunchKernelGGL(sample_bwd_kernel<kBasisBits>, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  if (variant == 1) hipLaunchKernelGGL(sample_bwd_full_kernel, dim3(n_wg), dim3(kThreads), 0, stream, a);
+  else hipLaunchKernelGGL(sample_bwd_kernel<kBasisBits>, dim3(n_wg), dim3(kThreads), 0, stream, a);
   return hipGetLastError() == hipSuccess ? GWS_OK : GWS_ERR_LAUNCH;
 }
 

@@ -107,9 +107,12 @@ __device__ __forceinline__ void store_codes(GWS_GLOBAL uint8_t* row, uint32_t co
 // BT_PRE: the caller has already fetched this lane's block parameter (bt_pre), as a wavefront that works
 // through several tiles alone does together with the tile loads, so that its latency is not paid per tile.
 // BASIS: kBasisBits is the method's noise (Sec. 3.4); the other two are the comparison bases (no MX form).
+// rows_part: the row-only share of the lane's four Philox calls, when the caller keeps it across column tiles
+// (philox_rows of the rows d.row0 + 32 by + lane / 8 + 8 i); NULL: every call is computed on its own.
 template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false, int BASIS = kBasisBits>
 __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
-                                         uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f) {
+                                         uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f,
+                                         const PhiloxRows* rows_part = nullptr) {
   const uint32_t row_base = by * 32;
   const uint32_t gc = lane & 7, r0 = lane >> 3;
   const uint32_t col = col_base + gc * 8;
@@ -151,17 +154,19 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   // ---- noise, add, round, cast, store ----
   const uint32_t cg = d.cg0 + (col >> 3);
   static_assert(BASIS == kBasisBits || !MX, "the comparison bases have no MX output");
-  // the four BF16 sums of one group (before the cast), whatever the basis
-  auto sampled_group = [&](const u32x4 w, uint32_t row, uint32_t (&pk)[4]) {
+  Philox4 x4[4];
+  if (rows_part != nullptr) philox_four_rows(cg, *rows_part, step_lo, step_hi, d.seed_lo, d.seed_hi, x4);
+  // the four BF16 sums of group i (before the cast), whatever the basis
+  auto sampled_group = [&](const u32x4 w, uint32_t row, int i, uint32_t (&pk)[4]) {
     if constexpr (BASIS == kBasisBits) {
-      const Noise n = group_noise(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const Noise n = rows_part != nullptr ? noise_planes(x4[i]) : group_noise(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
       const GroupMagnitudes g = group_magnitudes(n);
       pk[0] = sampled_pair<0>(w[0], g, n, b);
       pk[1] = sampled_pair<1>(w[1], g, n, b);
       pk[2] = sampled_pair<2>(w[2], g, n, b);
       pk[3] = sampled_pair<3>(w[3], g, n, b);
     } else {
-      const Philox4 x = philox4x32_10(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const Philox4 x = rows_part != nullptr ? x4[i] : philox4x32_10(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
       pk[0] = sampled_pair_basis<BASIS, 0>(w[0], x, b);
       pk[1] = sampled_pair_basis<BASIS, 1>(w[1], x, b);
       pk[2] = sampled_pair_basis<BASIS, 2>(w[2], x, b);
@@ -175,12 +180,12 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         if (!FULL && t.nv[i] == 0) continue;
         const uint32_t row = row_base + r0 + 8 * i;
         if constexpr (MX) {
-          const Noise n = group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+          const Noise n = rows_part != nullptr ? noise_planes(x4[i]) : group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
           const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, use_hw);
           store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
         } else {
           uint32_t pk[4];
-          sampled_group(t.v[i], d.row0 + row, pk);
+          sampled_group(t.v[i], d.row0 + row, i, pk);
           i16x2 chain = {0, 0};
           const u32x4 o = {cast_pair<FMT>(pk[0], b, use_hw, chain), cast_pair<FMT>(pk[1], b, use_hw, chain),
                            cast_pair<FMT>(pk[2], b, use_hw, chain), cast_pair<FMT>(pk[3], b, use_hw, chain)};
@@ -210,7 +215,7 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         continue;
       }
       uint32_t p4[4];
-      sampled_group(t.v[i], d.row0 + row_base + r0 + 8 * i, p4);
+      sampled_group(t.v[i], d.row0 + row_base + r0 + 8 * i, i, p4);
       pk[4 * i] = p4[0];
       pk[4 * i + 1] = p4[1];
       pk[4 * i + 2] = p4[2];

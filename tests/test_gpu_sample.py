@@ -272,3 +272,38 @@ def test_random_mixes_of_many_small_and_ragged_tensors(seed):
     for it, (_, scale) in zip(items, outs):
         it["scale"] = scale
     check_backward(items, step=seed, dw_mode="copy" if seed % 2 else "alias")
+
+
+def test_launch_shape_choices_give_the_same_bytes():
+    # include/gws_bench.h: the kernel variant (any-shape kernel, whole-tile kernel) and the column tiles a
+    # workgroup walks are launch-shape choices; forward and backward results may not depend on them.
+    # Whole-tile tensors (the whole-tile kernels run), a ragged one mixed in (the launch falls back to the
+    # any-shape kernel), a shard origin, and the bitwidth left per block.
+    shapes = [(64, 512), (96, 1280), (32, 256), (128, 768)]
+    for mix in (shapes, shapes + [(40, 300)]):
+        descs = []
+        for i, (r, c) in enumerate(mix):
+            t = synth.make_tensor(1500 + i, r, c, ld=(c + 7) // 8 * 8, device=DEV)
+            nbr, nbc = synth.n_blocks(r, c)
+            descs.append(gws.TensorDesc(rows=r, cols=c, ld=t["w"].stride(0), seed=oracle.derive_seed(6, i), row0=32 * i, col0=64 * i,
+                                        w=t["w"], w_hat=torch.zeros_like(t["w"]), bt=t["bt"], scale=torch.zeros(nbr, nbc, device=DEV),
+                                        g=t["g"], dw=t["g"], dbt=torch.zeros(nbr, nbc, device=DEV)))
+        outs = lambda: [x.clone() for d in descs for x in (d.w_hat, d.scale, d.dbt)]
+        gws.gws_sample_fwd(descs, gws.FMT_FP8_E4M3, 4)
+        gws.gws_sample_bwd(descs, 4)
+        torch.cuda.synchronize()
+        ref = outs()
+        for variant in (0, 1):
+            for per_x in (1, 2, 3, 5):
+                for d in descs:
+                    d.w_hat.zero_(), d.scale.zero_(), d.dbt.zero_()
+                gws.gws_sample_fwd_tuned(descs, gws.FMT_FP8_E4M3, 4, variant, per_x)
+                gws.gws_sample_bwd_tuned(descs, 4, variant, per_x)
+                torch.cuda.synchronize()
+                for k, (a, b) in enumerate(zip(outs(), ref)):
+                    # forward outputs bit for bit; dL/db_t too: both kernels add in the same order
+                    assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (len(mix), variant, per_x, k)
+    # and the reference itself is the oracle's
+    d = descs[1]
+    ref_q, ref_s = oracle.sample_fwd(synth.bits(d.w), d.bt.cpu().numpy(), oracle.FMT_FP8_E4M3, d.seed, 4, cols=d.cols, row0=d.row0, col0=d.col0)
+    assert (synth.bits(d.w_hat) == ref_q).all()
