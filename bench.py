@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="run only the precision x format sweep of config 4 and print its JSON")
+    ap.add_argument("--only-layer", action="store_true",
+                    help="run only the decoder-layer comparison (five GEMMs per layer, sampling separate / riding) and print its JSON")
     ap.add_argument("--only-bases", action="store_true",
                     help="run only the noise-basis comparison (forward unit benchmark) and print its JSON")
     ap.add_argument("--only-linear", action="store_true",
@@ -135,6 +137,9 @@ def main():
 
     if args.only_linear:
         print(json.dumps({"fused_linear": linear_bench(torch, gws, synth, dev)}))
+        return
+    if args.only_layer:
+        print(json.dumps({"decoder_layer_forward": layer_bench(torch, gws, synth, dev)}))
         return
     if args.only_bases:
         sh = synth.llama_1b_shapes()
@@ -268,6 +273,10 @@ def main():
             extras["fused_linear"] = linear_bench(torch, gws, synth, dev)
         except Exception as e:  # pragma: no cover
             extras["linear_error"] = repr(e)
+        try:
+            extras["decoder_layer_forward"] = layer_bench(torch, gws, synth, dev)
+        except Exception as e:  # pragma: no cover
+            extras["decoder_layer_error"] = repr(e)
         # Context only, derived from the figures above (nothing here is measured end to end): what share
         # of a training step the sampling of every weight would take if the step's GEMMs (6 FLOP per
         # parameter and token) ran at the plain BF16 GEMM rate measured above.
@@ -310,7 +319,7 @@ def empty_event_pair_ms(torch):
     return sorted(a.elapsed_time(b) for a, b in pairs)[len(pairs) // 2]
 
 
-def traffic_from_profile(workload, kernel="sample_fwd_kernel"):
+def traffic_from_profile(workload, kernel=r"sample_fwd\w*_kernel"):
     """HBM bytes per launch of `kernel` as the committed rocprofv3 --pmc summary of this workload states them
     (FETCH_SIZE and WRITE_SIZE runs of this script, each scaled by a 1 GiB plain device copy of the same run).
     Returns (bytes or None, where the figure comes from)."""
@@ -343,7 +352,7 @@ def roofline_block(res, fwd_bytes, bwd_bytes, pair_ms, workload):
     f_raw, f_corr, f_gbs, f_gbs_corr = one(res["fwd_ms"], fwd_bytes)
     b_raw, b_corr, b_gbs, b_gbs_corr = one(res["bwd_ms"], bwd_bytes)
     traffic, source = traffic_from_profile(workload)
-    return {"kernel": "sample_fwd_kernel<FP8_E4M3>", "bound": "hbm", "achieved": f_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    return {"kernel": "sample_fwd_full_kernel<FP8_E4M3>", "bound": "hbm", "achieved": f_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": f_gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
             "launch_ms": f_raw, "bytes_per_launch": fwd_bytes / nl,
             "achieved_event_overhead_removed": f_gbs_corr, "frac_event_overhead_removed": f_gbs_corr / HBM_PEAK_GBS,
@@ -352,7 +361,7 @@ def roofline_block(res, fwd_bytes, bwd_bytes, pair_ms, workload):
                       "call; the *_event_overhead_removed figures subtract the reading of an empty event pair first",
             "call_ms_between_events": res["fwd_ms"], "call_ms_between_events_median": res["fwd_ms_median"],
             "call_ms_between_events_min": res["fwd_ms_min"], "empty_event_pair_ms": pair_ms,
-            "bwd": {"kernel": "sample_bwd_kernel", "launch_ms": b_raw, "bytes_per_launch": bwd_bytes / nl,
+            "bwd": {"kernel": "sample_bwd_full_kernel", "launch_ms": b_raw, "bytes_per_launch": bwd_bytes / nl,
                     "call_ms_between_events": res["bwd_ms"], "call_ms_between_events_median": res["bwd_ms_median"],
                     "call_ms_between_events_min": res["bwd_ms_min"], "achieved": b_gbs, "frac": b_gbs / HBM_PEAK_GBS,
                     "achieved_event_overhead_removed": b_gbs_corr, "frac_event_overhead_removed": b_gbs_corr / HBM_PEAK_GBS,
@@ -543,6 +552,107 @@ def basis_step_bench(torch, gws, synth, dev, shapes, params):
     out["box_muller_over_ours"] = out["box_muller"]["ms_per_step"] / out["ours_bits"]["ms_per_step"]
     out["uniform_over_ours"] = out["uniform_bf16"]["ms_per_step"] / out["ours_bits"]["ms_per_step"]
     return out
+
+
+def layer_bench(torch, gws, synth, dev, tokens=8192, layers=4):
+    """The sampled-weight linear at the level the method is used: the five GEMMs of a Llama-style 1B decoder layer
+    (hidden 2048, fused q/k/v of 2560 outputs, SwiGLU intermediate 5632) over `tokens` tokens, `layers` layers in a
+    row.  Plain BF16 GEMMs on the stored weights against the same GEMMs on sampled weights, the sampling done
+      separate: by gws_linear_fwd (sampling kernel, then GEMM) for every weight;
+      riding:   inside the launch of an earlier GEMM wherever that GEMM's last round of tiles leaves compute units
+                idle (gws_gemm_bf16_sample_next_n): q/k/v's GEMM (320 tiles, 192 units idle in its second round)
+                carries w_o, w_gate and the next layer's w_qkv; gate's and up's GEMMs (704 tiles, 64 idle) carry
+                w_up and w_down; o's and down's GEMMs fill the chip exactly (256 tiles) and carry nothing.
+    Attention and the activation function are left out: every GEMM runs on a fixed input of its shape."""
+    H, QKV, FF = 2048, 2560, 5632
+    fmt = gws.FMT_FP8_E4M3
+    shapes = {"qkv": (H, QKV), "o": (H, H), "gate": (H, FF), "up": (H, FF), "down": (FF, H)}   # stored [K x N]
+    order = ["qkv", "o", "gate", "up", "down"]
+    x_h = synth.make_activation(60, tokens, H, device=dev)
+    x_ff = synth.make_activation(61, tokens, FF, device=dev)
+    outs = {n: torch.empty(tokens, shapes[n][1], dtype=torch.bfloat16, device=dev) for n in order}
+    inp = {"qkv": x_h, "o": x_h, "gate": x_h, "up": x_h, "down": x_ff}
+    W = []
+    for l in range(layers):
+        lw = {}
+        for k, n in enumerate(order):
+            r, c = shapes[n]
+            t = synth.make_tensor(70 + 5 * l + k, r, c, bt=6.0, device=dev, with_grad=False)
+            lw[n] = gws.TensorDesc(rows=r, cols=c, seed=gws.gws_derive_seed(2, 5 * l + k), w=t["w"], w_hat=torch.empty_like(t["w"]),
+                                   bt=t["bt"], scale=torch.empty(r // 32, c // 32, device=dev))
+        W.append(lw)
+    step = [0]
+
+    def plain():
+        for l in range(layers):
+            for n in order:
+                gws.gws_gemm_bf16(inp[n], W[l][n].w, outs[n])
+
+    def plain_torch():
+        for l in range(layers):
+            for n in order:
+                torch.matmul(inp[n], W[l][n].w, out=outs[n])
+
+    def plain_on_w_hat():            # the same GEMMs on weights sampled beforehand: what the sampling itself adds is
+        for l in range(layers):      # the difference to this (GEMM time depends on the operand values: fewer bits toggle)
+            for n in order:
+                gws.gws_gemm_bf16(inp[n], W[l][n].w_hat, outs[n])
+
+    def torch_on_w_hat():
+        for l in range(layers):
+            for n in order:
+                torch.matmul(inp[n], W[l][n].w_hat, out=outs[n])
+
+    def separate():
+        step[0] += 1
+        for l in range(layers):
+            for n in order:
+                gws.gws_linear_fwd(inp[n], W[l][n], outs[n], fmt, step[0])
+
+    # what each GEMM is asked to carry (the library decides what fits; the rest follows the GEMM as a launch)
+    def carried(l):
+        nxt_qkv = [W[l + 1]["qkv"]] if l + 1 < layers else []
+        return {"qkv": [W[l]["o"], W[l]["gate"]] + nxt_qkv, "o": [], "gate": [W[l]["up"]], "up": [W[l]["down"]], "down": []}
+
+    def riding():
+        step[0] += 1
+        gws.gws_sample_fwd([W[0]["qkv"]], fmt, step[0])
+        for l in range(layers):
+            c = carried(l)
+            for n in order:
+                gws.gws_gemm_bf16_sample_next_n(inp[n], W[l][n].w_hat, outs[n], c[n], fmt, step[0])
+
+    plan = {n: f"{gws.gws_ride_plan(tokens, shapes[n][0], shapes[n][1], carried(0)[n]) if carried(0)[n] else 0} of {len(carried(0)[n])} ride"
+            for n in order}
+    # the riding schedule produces the same sampled weights as gws_sample_fwd
+    riding()
+    ref = gws.TensorDesc(rows=H, cols=FF, seed=W[1]["up"].seed, w=W[1]["up"].w, w_hat=torch.empty_like(W[1]["up"].w),
+                         bt=W[1]["up"].bt, scale=torch.empty(H // 32, FF // 32, device=dev))
+    gws.gws_sample_fwd([ref], fmt, step[0])
+    torch.cuda.synchronize()
+    same = bool(torch.equal(ref.w_hat.view(torch.int16), W[1]["up"].w_hat.view(torch.int16)))
+    variants = {"plain": plain, "plain_torch": plain_torch, "plain_on_w_hat": plain_on_w_hat, "torch_on_w_hat": torch_on_w_hat,
+                "separate": separate, "riding": riding}
+    for fn in variants.values():
+        for _ in range(2):
+            fn()
+    bursts = {k: [] for k in variants}
+    for _ in range(9):
+        for k, fn in variants.items():
+            bursts[k].append(_time_ms(torch, fn, 3, warmup=1) / layers)
+    med = {k: sorted(v)[len(v) // 2] for k, v in bursts.items()}
+    best_plain = min(med["plain"], med["plain_torch"])
+    flop = 2.0 * tokens * sum(r * c for r, c in shapes.values())
+    return {"tokens": tokens, "layers_in_a_row": layers, "gemms_per_layer": {n: [tokens, shapes[n][0], shapes[n][1]] for n in order},
+            "ms_per_layer": med, "plain_TFLOPs": flop / med["plain"] / 1e9,
+            "separate_overhead_pct_vs_own_plain": 100.0 * (med["separate"] - med["plain"]) / med["plain"],
+            "riding_overhead_pct_vs_own_plain": 100.0 * (med["riding"] - med["plain"]) / med["plain"],
+            "separate_overhead_pct_vs_best_plain": 100.0 * (med["separate"] - best_plain) / best_plain,
+            "riding_overhead_pct_vs_best_plain": 100.0 * (med["riding"] - best_plain) / best_plain,
+            "riding_overhead_pct_vs_same_gemms_on_w_hat": 100.0 * (med["riding"] - med["plain_on_w_hat"]) / med["plain_on_w_hat"],
+            "separate_overhead_pct_vs_same_gemms_on_w_hat": 100.0 * (med["separate"] - med["plain_on_w_hat"]) / med["plain_on_w_hat"],
+            "carried_by_each_gemm": plan, "riding_matches_gws_sample_fwd": same,
+            "sampled_params_per_layer": sum(r * c for r, c in shapes.values())}
 
 
 def copy_ceiling(torch):

@@ -253,6 +253,17 @@ int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx,
                               void* y, int64_t ldy,
                               const gws_tensor* next, int fmt, uint64_t step, void* stream);
 
+/* The same for a list of weights (host array of n_next <= 64 descriptors, sampled as gws_sample_fwd(next, n_next,
+ * fmt, step) would): a forward pass that knows its layers can sample several coming weights under one GEMM whose
+ * last round of tiles leaves many compute units idle, and none under a GEMM whose tiles fill the chip exactly.
+ * As many weights as fit ride in the GEMM's launch, in the order given (at most four; riding several needs rows
+ * a multiple of 32 and columns a multiple of 256); the rest are sampled by one launch after the GEMM.  Same
+ * bytes either way.  n_next = 0 is gws_gemm_bf16.                                                        */
+int gws_gemm_bf16_sample_next_n(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                const void* w, int64_t N, int64_t ldw, int w_is_nk,
+                                void* y, int64_t ldy,
+                                const gws_tensor* next, int n_next, int fmt, uint64_t step, void* stream);
+
 /* The comparison systems of the paper's Sec. 4 behind the same interface: the same forward and
  * backward passes with R drawn from another noise basis.  The paper compares GaussWS with the same
  * pipeline on a BF16 U(-0.5, 0.5) basis (its "DiffQ" extension, Sec. 4 and Table 1) and, in the

@@ -37,6 +37,19 @@ int gws_sample_bwd_tuned(const gws_tensor* t, int n, uint64_t step, int variant,
 /* The same for gws_sample_fwd: variant -1 / 0 / 1 (whole-tile kernel), per_x as above.               */
 int gws_sample_fwd_tuned(const gws_tensor* t, int n, int fmt, uint64_t step, int variant, int per_x, void* stream);
 
+/* gws_gemm_bf16_sample_next with the riding forced: the GEMM (none at all if M == 0) is followed in the same
+ * grid by `extra_workgroups` (1 .. 4096) workgroups that sample `next` (rows a multiple of 32, columns of 64),
+ * whatever the library's own estimate of whether the sampling fits beside the GEMM's last round says.
+ * rider: 0 = the riding loop for any such weight, 1 = the loop for weights of whole 32 x 256 tiles (falls back
+ * to 0 for other weights).  Same bytes as gws_gemm_bf16_sample_next.                                        */
+int gws_gemm_bf16_ride_probe(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                             int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int fmt, uint64_t step,
+                             int extra_workgroups, int rider, void* stream);
+
+/* How many of the weights next[0 .. n_next) gws_gemm_bf16_sample_next_n would let ride in the launch of an
+ * M x K x N GEMM on the current device (a prefix of the list); host function, launches nothing.            */
+int gws_ride_plan(int64_t M, int64_t K, int64_t N, const gws_tensor* next, int n_next);
+
 #ifdef __cplusplus
 }
 #endif

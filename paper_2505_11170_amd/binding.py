@@ -20,10 +20,10 @@ BASIS_BITS, BASIS_UNIFORM_BF16, BASIS_BOX_MULLER = 0, 1, 2
 
 # include/gws.h (the method) and include/gws_bench.h (measurement aids)
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode",
-           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_noise_packed",
+           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_gemm_bf16_sample_next_n", "gws_noise_packed",
            "gws_sample_fwd_basis", "gws_sample_bwd_basis", "gws_noise_basis",
            "gws_derive_seed", "gws_status_string", "gws_version")
-BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax", "gws_sample_bwd_tuned", "gws_sample_fwd_tuned")
+BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax", "gws_sample_bwd_tuned", "gws_sample_fwd_tuned", "gws_gemm_bf16_ride_probe", "gws_ride_plan")
 
 
 class GwsError(RuntimeError):
@@ -128,6 +128,12 @@ def load_library() -> ctypes.CDLL:
     L.gws_gemm_bf16_sample_next.restype = ci
     L.gws_copy_tiles.argtypes = [tp, ci, vp]
     L.gws_copy_tiles.restype = ci
+    L.gws_gemm_bf16_sample_next_n.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, tp, ci, ci, u64, vp]
+    L.gws_gemm_bf16_sample_next_n.restype = ci
+    L.gws_ride_plan.argtypes = [i64, i64, i64, tp, ci]
+    L.gws_ride_plan.restype = ci
+    L.gws_gemm_bf16_ride_probe.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, tp, ci, u64, ci, ci, vp]
+    L.gws_gemm_bf16_ride_probe.restype = ci
     L.gws_sample_fwd_tuned.argtypes = [tp, ci, ci, u64, ci, ci, vp]
     L.gws_sample_fwd_tuned.restype = ci
     L.gws_sample_bwd_tuned.argtypes = [tp, ci, u64, ci, ci, vp]
@@ -366,6 +372,38 @@ def gws_gemm_bf16_sample_next(x, w, y, nxt: Optional[TensorDesc], fmt: int, step
     _check(L.gws_gemm_bf16_sample_next(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
                                        _p(y), int(y.stride(0)), arr, int(fmt), int(step), _stream(stream)),
            "gws_gemm_bf16_sample_next")
+
+
+def gws_gemm_bf16_sample_next_n(x, w, y, nxt, fmt: int, step: int, w_is_nk: bool = False, stream=None) -> None:
+    """``gws_gemm_bf16`` with ``gws_sample_fwd(nxt, fmt, step)`` of a list of weights riding along where that pays."""
+    L = load_library()
+    M, K = int(x.shape[0]), int(x.shape[1])
+    N = int(w.shape[0] if w_is_nk else w.shape[1])
+    arr, n = _as_c(nxt)
+    _check(L.gws_gemm_bf16_sample_next_n(_p(x), M, K, int(x.stride(0)), _p(w), N, int(w.stride(0)), int(bool(w_is_nk)),
+                                         _p(y), int(y.stride(0)), arr, n, int(fmt), int(step), _stream(stream)),
+           "gws_gemm_bf16_sample_next_n")
+
+
+def gws_ride_plan(M: int, K: int, N: int, nxt) -> int:
+    """How many of ``nxt`` would ride in the launch of an M x K x N GEMM (a measurement aid)."""
+    arr, n = _as_c(nxt)
+    return int(load_library().gws_ride_plan(int(M), int(K), int(N), arr, n))
+
+
+def gws_gemm_bf16_ride_probe(x, w, y, nxt: TensorDesc, fmt: int, step: int, extra_workgroups: int, rider: int = 1,
+                             w_is_nk: bool = False, stream=None) -> None:
+    """``gws_gemm_bf16_sample_next`` with the riding forced (a measurement aid); ``x=None`` launches the riders alone."""
+    L = load_library()
+    if x is None:
+        M = K = N = ldx = ldw = ldy = 0
+    else:
+        M, K = int(x.shape[0]), int(x.shape[1])
+        N = int(w.shape[0] if w_is_nk else w.shape[1])
+        ldx, ldw, ldy = int(x.stride(0)), int(w.stride(0)), int(y.stride(0))
+    _check(L.gws_gemm_bf16_ride_probe(_p(x), M, K, ldx, _p(w), N, ldw, int(bool(w_is_nk)), _p(y), ldy, _marshal([nxt]),
+                                      int(fmt), int(step), int(extra_workgroups), int(rider), _stream(stream)),
+           "gws_gemm_bf16_ride_probe", "gws_ride_plan")
 
 
 def gws_copy_tiles(t: Sequence[TensorDesc], stream=None) -> None:

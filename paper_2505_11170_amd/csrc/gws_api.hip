@@ -552,13 +552,71 @@ int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* 
   return launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
 }
 
-int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
-                              int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int fmt, uint64_t step,
-                              void* stream) {
-  if (!next) return gws_gemm_bf16(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, stream);
+// How many of the weights next[0 .. n_next) ride in the launch of the GEMM g (a prefix of the list), with the riders'
+// descriptors, the number of extra workgroups and the riding loop to use.
+// Ride along when the 256-tile GEMM leaves compute units without a tile in its last round and the sampling fits
+// beside that round.  Measured on MI355X: a riding wavefront (one per SIMD, the GEMM's register allocation) takes
+// about 1.8 us per 32 x 64 tile in ride_tiles and 2.1 us in sample_tiles; a GEMM tile about 1.6 us per K-step of 64.
+static int plan_ride(const GemmArgs& g, bool gemm_empty, int64_t K, const gws_tensor* next, int n_next, int force_extra,
+                     int rider, RideList& r, uint32_t& idle, int& use_rider) {
+  memset(&r, 0, sizeof r);
+  idle = 0;
+  use_rider = 1;
+  const bool gemm_rides = force_extra >= 0 ? (gemm_empty || gemm256_applicable(g)) : (!gemm_empty && gemm256_applicable(g));
+  if (!gemm_rides) return 0;
+  const int cus = compute_units();
+  const uint64_t tiles = gemm_empty ? 0 : (uint64_t)(g.M / 256) * (uint64_t)(g.N / 256);
+  idle = cus > 0 ? (uint32_t)((cus - tiles % cus) % cus) : 0u;
+  if (force_extra >= 0) idle = (uint32_t)force_extra;
+  if (idle == 0) return 0;
+  const double t_tile_us = (double)(K / 64) * 1.6 + 5.0;
+  int n_riding = 0;
+  double t_sample_us = 0.0;
+  uint32_t begin = 0;
+  for (int i = 0; i < n_next && n_riding < kMaxRide; ++i) {
+    const gws_tensor& t = next[i];
+    if (t.rows == 0 || t.cols == 0 || (t.rows & 31) != 0 || (t.cols & 63) != 0) break;
+    const bool wide = (t.cols & 255) == 0 && rider != 0;
+    if (!wide && i > 0) break;                                                      // sample_tiles takes one weight
+    const double units = (double)(t.rows / 32) * (double)(t.cols / 64);             // wavefront tiles
+    const double add = units / (4.0 * idle) * (wide ? 1.8 : 2.1);
+    // with a margin: a riding part that outlasts the tiles costs more than the launch it saves
+    if (force_extra < 0 && t_sample_us + add > (wide ? 0.8 : 0.6) * t_tile_us) break;
+    t_sample_us += add;
+    TileDesc& d = r.d[n_riding];
+    memset(&d, 0, sizeof d);
+    d.p0 = t.w; d.p1 = t.w_hat; d.p2 = (void*)t.bt; d.p3 = t.scale; d.p4 = nullptr;
+    fill_common(d, t, 1);
+    d.b_target = 0.0f; d.b_delta = 1.0f; d.lambda_m = 0.0f;
+    d.first_wg = begin;
+    r.begin[n_riding] = begin;
+    begin += (uint32_t)((t.rows / 32) * (t.cols / 256));
+    ++n_riding;
+    if (!wide) {
+      use_rider = 0;
+      break;
+    }
+  }
+  for (int j = n_riding; j <= kMaxRide; ++j) r.begin[j] = begin;
+  r.n = (uint32_t)n_riding;
+  return n_riding;
+}
+
+// The plain GEMM with the forward sampling of `n_next` weights: as many of them as fit ride in the GEMM's launch
+// (in the order given), the others are sampled by one launch of the sampling kernel after it.
+// force_extra >= 0: ride with that many extra workgroups whatever the estimate says (measurement); rider: the riding
+// loop (launch_gemm256_ride), -1 = the library's choice.
+static int gemm_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                            int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int n_next, int fmt, uint64_t step,
+                            int force_extra, int rider, void* stream) {
+  if (n_next < 0 || n_next > 64) return GWS_ERR_SHAPE;
+  if (n_next == 0) return gws_gemm_bf16(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, stream);
+  if (!next) return GWS_ERR_NULL;
   if (fmt != GWS_FMT_BF16 && fmt != GWS_FMT_FP8_E4M3 && fmt != GWS_FMT_FP6_E3M2) return GWS_ERR_FORMAT;
-  int rc = check_fwd(*next);
-  if (rc != GWS_OK) return rc;
+  for (int i = 0; i < n_next; ++i) {
+    int rc = check_fwd(next[i]);
+    if (rc != GWS_OK) return rc;
+  }
   // the GEMM's own argument rules (as gws_gemm_bf16), checked before anything is launched
   if (M < 0 || K < 0 || N < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
   const bool gemm_empty = (M == 0 || N == 0);
@@ -569,45 +627,67 @@ int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx, 
         ldx >= (int64_t)1 << 31 || ldy >= (int64_t)1 << 31 || ldw >= (int64_t)1 << 31) return GWS_ERR_SHAPE;
     if (!x || !w || !y) return GWS_ERR_NULL;
     if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return GWS_ERR_ALIGN;
-    // the sampled weight must not be an operand or the result of this GEMM
-    const size_t hat_bytes = (size_t)next->rows * next->ld * 2;
-    if (next->rows > 0 && next->cols > 0 &&
-        (overlap2(next->w_hat, hat_bytes, w, (size_t)(w_is_nk ? N : K) * ldw * 2) ||
-         overlap2(next->w_hat, hat_bytes, x, (size_t)M * ldx * 2) || overlap2(next->w_hat, hat_bytes, y, (size_t)M * ldy * 2)))
-      return GWS_ERR_ALIAS;
+    // a sampled weight must not be an operand or the result of this GEMM
+    for (int i = 0; i < n_next; ++i) {
+      const size_t hat_bytes = (size_t)next[i].rows * next[i].ld * 2;
+      if (next[i].rows > 0 && next[i].cols > 0 &&
+          (overlap2(next[i].w_hat, hat_bytes, w, (size_t)(w_is_nk ? N : K) * ldw * 2) ||
+           overlap2(next[i].w_hat, hat_bytes, x, (size_t)M * ldx * 2) || overlap2(next[i].w_hat, hat_bytes, y, (size_t)M * ldy * 2)))
+        return GWS_ERR_ALIAS;
+    }
   }
-  const bool next_empty = (next->rows == 0 || next->cols == 0);
   GemmArgs g;
   memset(&g, 0, sizeof g);
   g.x = (const uint16_t*)x; g.w = (const uint16_t*)w; g.y = (uint16_t*)y;
   g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
   g.ldx = (uint32_t)ldx; g.ldw = (uint32_t)ldw; g.ldy = (uint32_t)ldy;
-  // Ride along when the 256-tile GEMM leaves compute units without a tile in its last round and the
-  // sampling fits beside that round: measured, a riding wavefront (one per SIMD, the GEMM's register
-  // allocation, beside the GEMM's memory traffic) takes about 3.8 us per 32 x 64 tile, a GEMM tile
-  // about 1.6 us per K-step of 64.
-  if (!gemm_empty && !next_empty && gemm256_applicable(g) && (next->rows & 31) == 0 && (next->cols & 63) == 0) {
-    const int cus = compute_units();
-    const uint64_t tiles = (uint64_t)(M / 256) * (uint64_t)(N / 256);
-    const uint32_t idle = cus > 0 ? (uint32_t)((cus - tiles % cus) % cus) : 0u;
-    if (idle > 0) {
-      const double units = (double)(next->rows / 32) * (double)(next->cols / 64);     // wavefront tiles
-      const double t_sample_us = units / (4.0 * idle) * 3.8, t_tile_us = (double)(K / 64) * 1.6 + 5.0;
-      if (t_sample_us <= 0.6 * t_tile_us) {   // with a margin: a riding part that outlasts the tiles costs more than a launch
-        TileDesc d;
-        memset(&d, 0, sizeof d);
-        d.p0 = next->w; d.p1 = next->w_hat; d.p2 = (void*)next->bt; d.p3 = next->scale; d.p4 = nullptr;
-        fill_common(d, *next, 1);
-        d.b_target = 0.0f; d.b_delta = 1.0f; d.lambda_m = 0.0f;
-        return launch_gemm256_ride(g, w_is_nk, d, fmt, step, idle, (hipStream_t)stream);
-      }
-    }
-  }
-  if (!gemm_empty) {
-    rc = launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+  if (gemm_empty) g.M = g.N = 0;
+
+  RideList r;
+  uint32_t idle = 0;
+  int use_rider = 1;
+  const int n_riding = plan_ride(g, gemm_empty, K, next, n_next, force_extra, rider, r, idle, use_rider);   // the first n_riding ride
+  if (n_riding > 0) {
+    int rc = launch_gemm256_ride(g, w_is_nk, r, fmt, step, idle, use_rider, (hipStream_t)stream);
     if (rc != GWS_OK) return rc;
   }
-  return run_batched(next, 1, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, /*keep=*/true);
+  if (n_riding == 0 && !gemm_empty) {
+    int rc = launch_gemm(g, w_is_nk, 0, GWS_FMT_BF16, (hipStream_t)stream);
+    if (rc != GWS_OK) return rc;
+  }
+  if (n_riding == n_next) return GWS_OK;
+  return run_batched(next + n_riding, n_next - n_riding, nullptr, nullptr, true, fmt, step, (hipStream_t)stream, /*keep=*/true);
+}
+
+int gws_gemm_bf16_sample_next(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                              int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int fmt, uint64_t step,
+                              void* stream) {
+  return gemm_sample_next(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, next, next ? 1 : 0, fmt, step, -1, -1, stream);
+}
+
+int gws_gemm_bf16_sample_next_n(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                                int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int n_next, int fmt,
+                                uint64_t step, void* stream) {
+  return gemm_sample_next(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, next, n_next, fmt, step, -1, -1, stream);
+}
+
+int gws_ride_plan(int64_t M, int64_t K, int64_t N, const gws_tensor* next, int n_next) {
+  if (!next || n_next <= 0 || M <= 0 || N <= 0 || K <= 0) return 0;
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
+  RideList r;
+  uint32_t idle = 0;
+  int use_rider = 1;
+  return plan_ride(g, false, K, next, n_next, -1, -1, r, idle, use_rider);
+}
+
+int gws_gemm_bf16_ride_probe(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,
+                             int w_is_nk, void* y, int64_t ldy, const gws_tensor* next, int fmt, uint64_t step,
+                             int extra_workgroups, int rider, void* stream) {
+  if (!next || extra_workgroups < 1 || extra_workgroups > 4096 || rider < 0 || rider > 1) return GWS_ERR_SHAPE;
+  if ((next->rows & 31) != 0 || (next->cols & 63) != 0) return GWS_ERR_SHAPE;
+  return gemm_sample_next(x, M, K, ldx, w, N, ldw, w_is_nk, y, ldy, next, 1, fmt, step, extra_workgroups, rider, stream);
 }
 
 // Philox4x32-10 on the host, for the seed derivation only.

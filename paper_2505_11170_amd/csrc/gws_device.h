@@ -60,7 +60,8 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 //   round 1: M0 * c0 depends on the row only (PhiloxRows: kept across the column tiles a wavefront walks),
 //            M1 * c2 on the column group only;
 //   round 2: M0 * c0 depends on the column group only; from M1 * c2 on everything depends on both.
-// 63 multiplies per four calls instead of 80 (67 with the row part), same bits as philox4x32_10.
+// 63 multiplies per four calls instead of 80 (67 with the row part), same bits as philox4x32_10:
+// philox_rows once per wavefront, philox_cols once per tile, philox_row per call.
 struct PhiloxRows {
   uint32_t hi[4], lo[4];   // M0 * (c0 after round 0) for the four rows
 };
@@ -77,36 +78,82 @@ __device__ __forceinline__ PhiloxRows philox_rows(const uint32_t (&row)[4], uint
   return r;
 }
 
-__device__ __forceinline__ void philox_four_rows(uint32_t cg, const PhiloxRows& rp, uint32_t step_lo, uint32_t step_hi,
-                                                 uint32_t k0, uint32_t k1, Philox4 (&out)[4]) {
-  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+// The column-group share of the first three rounds (four registers), then one call per row.
+struct PhiloxCols {
+  uint32_t c3_1, c1_2, hi_f, c3_3;
+};
+
+__device__ __forceinline__ PhiloxCols philox_cols(uint32_t cg, uint32_t step_lo, uint32_t step_hi, uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u;
   const uint32_t c1_1 = (uint32_t)((uint64_t)M1 * step_lo);                      // round 0, uniform
   const uint64_t b = (uint64_t)M0 * cg;                                          // round 0, column group
-  const uint32_t c2_1 = xor3((uint32_t)(b >> 32), step_hi, k1), c3_1 = (uint32_t)b;
+  const uint32_t c2_1 = xor3((uint32_t)(b >> 32), step_hi, k1);
   const uint64_t c = (uint64_t)M1 * c2_1;                                        // round 1, column group
-  const uint32_t c0_2 = xor3((uint32_t)(c >> 32), c1_1, k0 + W0), c1_2 = (uint32_t)c;
+  const uint32_t c0_2 = xor3((uint32_t)(c >> 32), c1_1, k0 + W0);
   const uint64_t f = (uint64_t)M0 * c0_2;                                        // round 2, column group
-  const uint32_t hi_f = (uint32_t)(f >> 32), c3_3 = (uint32_t)f;
+  return PhiloxCols{(uint32_t)b, (uint32_t)c, (uint32_t)(f >> 32), (uint32_t)f};
+}
+
+// Call i of the four: the row share joins in round 1.
+__device__ __forceinline__ Philox4 philox_row(const PhiloxCols& pc, const PhiloxRows& rp, int i, uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  const uint32_t c2_2 = xor3(rp.hi[i], pc.c3_1, k1 + W1), c3_2 = rp.lo[i];       // round 1
+  const uint64_t e = (uint64_t)M1 * c2_2;                                        // round 2
+  uint32_t c0 = xor3((uint32_t)(e >> 32), pc.c1_2, k0 + 2 * W0), c1 = (uint32_t)e;
+  uint32_t c2 = xor3(pc.hi_f, c3_2, k1 + 2 * W1), c3 = pc.c3_3;
+  uint32_t ka = k0 + 3 * W0, kb = k1 + 3 * W1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t c2_2 = xor3(rp.hi[i], c3_1, k1 + W1), c3_2 = rp.lo[i];        // round 1, row part joins
-    const uint64_t e = (uint64_t)M1 * c2_2;                                      // round 2
-    uint32_t c0 = xor3((uint32_t)(e >> 32), c1_2, k0 + 2 * W0), c1 = (uint32_t)e;
-    uint32_t c2 = xor3(hi_f, c3_2, k1 + 2 * W1), c3 = c3_3;
-    uint32_t ka = k0 + 3 * W0, kb = k1 + 3 * W1;
-#pragma unroll
-    for (int r = 3; r < 10; ++r) {
-      const uint64_t p0 = (uint64_t)M0 * c0, p1 = (uint64_t)M1 * c2;
-      const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, ka), n2 = xor3((uint32_t)(p0 >> 32), c3, kb);
-      c1 = (uint32_t)p1;
-      c3 = (uint32_t)p0;
-      c0 = n0;
-      c2 = n2;
-      ka += W0;
-      kb += W1;
-    }
-    out[i] = Philox4{c0, c1, c2, c3};
+  for (int r = 3; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)M0 * c0, p1 = (uint64_t)M1 * c2;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, ka), n2 = xor3((uint32_t)(p0 >> 32), c3, kb);
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    ka += W0;
+    kb += W1;
   }
+  return Philox4{c0, c1, c2, c3};
+}
+
+// The calls of two tiles (column groups pc[0], pc[1]; the same four rows) advanced round by round together: for a
+// wavefront that has its SIMD to itself this is what keeps the vector ALU fed (sixteen independent multiplies per
+// round instead of two dependent chains).
+__device__ __forceinline__ void philox_two_tiles(const PhiloxCols (&pc)[2], const PhiloxRows& rp, uint32_t k0, uint32_t k1,
+                                                 Philox4 (&out)[2][4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t c0[8], c1[8], c2[8], c3[8];
+  uint64_t e[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) e[k] = (uint64_t)M1 * xor3(rp.hi[k & 3], pc[k >> 2].c3_1, k1 + W1);   // rounds 1 and 2
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    c0[k] = xor3((uint32_t)(e[k] >> 32), pc[k >> 2].c1_2, k0 + 2 * W0);
+    c1[k] = (uint32_t)e[k];
+    c2[k] = xor3(pc[k >> 2].hi_f, rp.lo[k & 3], k1 + 2 * W1);
+    c3[k] = pc[k >> 2].c3_3;
+  }
+  uint32_t ka = k0 + 3 * W0, kb = k1 + 3 * W1;
+#pragma unroll
+  for (int r = 3; r < 10; ++r) {
+    uint64_t p0[8], p1[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      p0[k] = (uint64_t)M0 * c0[k];
+      p1[k] = (uint64_t)M1 * c2[k];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      c0[k] = xor3((uint32_t)(p1[k] >> 32), c1[k], ka);
+      c2[k] = xor3((uint32_t)(p0[k] >> 32), c3[k], kb);
+      c1[k] = (uint32_t)p1[k];
+      c3[k] = (uint32_t)p0[k];
+    }
+    ka += W0;
+    kb += W1;
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) out[k >> 2][k & 3] = Philox4{c0[k], c1[k], c2[k], c3[k]};
 }
 
 // ---------------------------------------------------------------------------

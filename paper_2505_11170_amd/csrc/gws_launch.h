@@ -87,10 +87,20 @@ constexpr int kFusedInOperand = 2;
 int launch_gemm(const GemmArgs& g, int w_is_nk, int fused, int fmt, hipStream_t stream);
 bool gemm256_applicable(const GemmArgs& g);
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream);
-// the 256-tile GEMM followed, in the same grid, by `extra` workgroups that sample the weight `d`
-// (rows a multiple of 32, columns of 64) as the forward pass does
-int launch_gemm256_ride(const GemmArgs& g, int w_is_nk, const TileDesc& d, int fmt, uint64_t step, uint32_t extra,
-                        hipStream_t stream);
+// Weights whose forward sampling rides in a GEMM's launch: descriptors as the forward pass fills them, with
+// first_wg = the weight's first 32 x 256 tile in the riders' numbering (rider 1); begin[j] = that number again for
+// j < n and the total for every j >= n (so that a search over begin[1..] needs no n).
+constexpr int kMaxRide = 4;
+struct RideList {
+  TileDesc d[kMaxRide];
+  uint32_t begin[kMaxRide + 1];
+  uint32_t n;
+};
+// the 256-tile GEMM (none if g.M == 0) followed, in the same grid, by `extra` workgroups that sample the weights of
+// `r` as the forward pass does; rider: 0 = sample_tiles on r.d[0] alone (rows a multiple of 32, columns of 64),
+// 1 = ride_tiles (every weight: rows a multiple of 32, columns of 256)
+int launch_gemm256_ride(const GemmArgs& g, int w_is_nk, const RideList& r, int fmt, uint64_t step, uint32_t extra,
+                        int rider, hipStream_t stream);
 int compute_units();   // of the current device; 0 if the query fails
 // Weight-gradient GEMM (gws_gemm256_tn.hip): y[M x N] = x^T * w with x [K x M], w [K x N]
 // row-major (K = the contraction length); with_dbt adds Eq. 4's block reduction on y.

@@ -263,12 +263,11 @@ __global__ __launch_bounds__(kThreads) void sample_bwd_full_kernel(const LaunchA
   load4(bx0);
   for (uint32_t bx = bx0; bx < bx_end; ++bx) {
     const uint32_t col = bx * kTileCols + wave * 64 + gc * 8;
-    Philox4 x[4];
-    philox_four_rows(d.cg0 + (col >> 3), rp, a.step_lo, a.step_hi, d.seed_lo, d.seed_hi, x);
+    const PhiloxCols pc = philox_cols(d.cg0 + (col >> 3), a.step_lo, a.step_hi, d.seed_lo, d.seed_hi);
     // sum_{b_l}(g .* R) as sum(g .* 2R) / 2: exact products, fixed order (see bwd_tile)
     float acc = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc = dot_group_2r(v[i], noise_planes(x[i]), acc);
+    for (int i = 0; i < 4; ++i) acc = dot_group_2r(v[i], noise_planes(philox_row(pc, rp, i, d.seed_lo, d.seed_hi)), acc);
     acc = block_sum_f32(acc) * 0.5f;
     if (writer) {
       const size_t blk = (size_t)by * nbc + (col >> 5);

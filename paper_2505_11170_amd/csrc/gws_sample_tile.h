@@ -100,39 +100,41 @@ __device__ __forceinline__ void store_codes(GWS_GLOBAL uint8_t* row, uint32_t co
   }
 }
 
-// STREAM: w_hat is written with streaming (non-temporal) stores, right for a pass
-// that is not consumed at once; off, the stores stay in cache for a reader that follows.
-// MX: the output is element codes (p1, row stride ldc) and E8M0 block scales (p4)
-// instead of the BF16 container.
-// BT_PRE: the caller has already fetched this lane's block parameter (bt_pre), as a wavefront that works
-// through several tiles alone does together with the tile loads, so that its latency is not paid per tile.
-// BASIS: kBasisBits is the method's noise (Sec. 3.4); the other two are the comparison bases (no MX form).
-// rows_part: the row-only share of the lane's four Philox calls, when the caller keeps it across column tiles
-// (philox_rows of the rows d.row0 + 32 by + lane / 8 + 8 i); NULL: every call is computed on its own.
-template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false, int BASIS = kBasisBits>
-__device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
-                                         uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f,
-                                         const PhiloxRows* rows_part = nullptr) {
-  const uint32_t row_base = by * 32;
+// The forward pass on one wavefront tile, in two phases.
+//
+// tile_scale: a = max|w| of the lane's block (exact), the block's scale and cast constants.
+//   BT_PRE: the caller has already fetched this lane's block parameter (bt_pre), as a wavefront that works
+//   through several tiles alone does together with the tile loads, so that its latency is not paid per tile.
+//   STORE: the block's writer lane stores scale (and, MX, the E8M0 block scale) here; off, the caller does.
+// tile_apply: noise, add, round, cast, store.
+//   STREAM: w_hat is written with streaming (non-temporal) stores, right for a pass that is not consumed at
+//   once; off, the stores stay in cache for a reader that follows.
+//   MX: the output is element codes (p1, row stride ldc) and E8M0 block scales (p4) instead of the BF16 container.
+//   BASIS: kBasisBits is the method's noise (Sec. 3.4); the other two are the comparison bases (no MX form).
+//   USE_HW: FP8-E4M3 through the hardware converters (the caller has shown that no block of the wavefront can
+//   overflow); off, the arithmetic cast.  Same bits either way where both apply.
+//   rows_part: the row-only share of the lane's four Philox calls, when the caller keeps it across column tiles
+//   (philox_rows of the rows d.row0 + 32 by + lane / 8 + 8 i); bits: the four calls' results themselves, when
+//   the caller has them already; both NULL: every call is computed on its own.
+// Neither phase branches when FULL and !STORE, so a caller that works on several tiles at once gets straight-line
+// code it can interleave.
+template <int FMT, bool FULL, bool MX, bool BT_PRE, bool STORE>
+__device__ __forceinline__ BlockScale tile_scale(const TileDesc& d, Tile& t, uint32_t by, uint32_t col_base, uint32_t lane,
+                                                 float bt_pre) {
   const uint32_t gc = lane & 7, r0 = lane >> 3;
-  const uint32_t col = col_base + gc * 8;
-  GWS_GLOBAL uint16_t* __restrict__ w_hat = global_ptr<uint16_t>(d.p1);
   const GWS_GLOBAL float* __restrict__ bt = global_ptr<float>(d.p2);
   GWS_GLOBAL float* __restrict__ scale = global_ptr<float>(d.p3);
-
   if (!FULL) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (t.nv[i] < 8) t.v[i] = mask_group(t.v[i], t.nv[i]);  // elements past cols do not exist
   }
-
   // ---- a = max_{b_l}|w| on the magnitude bits (exact) ----
   uint32_t m = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) m = absmax_pk(t.v[i], m);
   m = max(m & 0xFFFFu, m >> 16);
   const uint32_t a16 = block_max_u32(m);
-
   // ---- per-block scale ----
   const uint32_t nbc = (d.cols + 31) >> 5;
   const uint32_t bcol = (col_base >> 5) + (gc >> 2);
@@ -143,68 +145,78 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
   BlockScale b = block_scale(a16, btv);
   if (FMT == 1) cast_constants<8, -6>(a16, b);
   if (FMT == 2) cast_constants<4, -2>(a16, b);
-  if (block_exists && (gc & 3) == 0 && r0 == 0) {
+  if (STORE && block_exists && (gc & 3) == 0 && r0 == 0) {
     scale[(size_t)by * nbc + bcol] = b.s32;
     // shared exponent of the block: biased exponent of X; X = 1 for an all-zero block
     if (MX) global_ptr<uint8_t>(d.p4)[(size_t)by * nbc + bcol] = a16 ? (uint8_t)(__float_as_uint(b.x_scale) >> 23) : (uint8_t)127;
   }
-  // hardware FP8 converters only if neither block of this wavefront can overflow
-  const bool hw = (FMT == 1) && (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0);
+  return b;
+}
 
-  // ---- noise, add, round, cast, store ----
-  const uint32_t cg = d.cg0 + (col >> 3);
+template <int FMT, bool FULL, bool STREAM, bool MX, int BASIS, bool USE_HW>
+__device__ __forceinline__ void tile_apply(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, const Tile& t,
+                                           const BlockScale& b, uint32_t by, uint32_t col_base, uint32_t lane,
+                                           const PhiloxRows* rows_part, const Philox4* bits) {
   static_assert(BASIS == kBasisBits || !MX, "the comparison bases have no MX output");
-  Philox4 x4[4];
-  if (rows_part != nullptr) philox_four_rows(cg, *rows_part, step_lo, step_hi, d.seed_lo, d.seed_hi, x4);
+  static_assert(!USE_HW || FMT == 1, "hardware converters by choice exist for FP8-E4M3 only");
+  const uint32_t row_base = by * 32;
+  const uint32_t gc = lane & 7, r0 = lane >> 3;
+  const uint32_t col = col_base + gc * 8;
+  GWS_GLOBAL uint16_t* __restrict__ w_hat = global_ptr<uint16_t>(d.p1);
+  const uint32_t cg = d.cg0 + (col >> 3);
+  PhiloxCols pc = {};
+  if (bits == nullptr && rows_part != nullptr) pc = philox_cols(cg, step_lo, step_hi, d.seed_lo, d.seed_hi);
+  auto bits_of = [&](uint32_t row, int i) {   // the 128 bits of the lane's group i (row = its global row)
+    return bits != nullptr         ? bits[i]
+           : rows_part != nullptr ? philox_row(pc, *rows_part, i, d.seed_lo, d.seed_hi)
+                                   : philox4x32_10(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+  };
   // the four BF16 sums of group i (before the cast), whatever the basis
   auto sampled_group = [&](const u32x4 w, uint32_t row, int i, uint32_t (&pk)[4]) {
     if constexpr (BASIS == kBasisBits) {
-      const Noise n = rows_part != nullptr ? noise_planes(x4[i]) : group_noise(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const Noise n = noise_planes(bits_of(row, i));
       const GroupMagnitudes g = group_magnitudes(n);
       pk[0] = sampled_pair<0>(w[0], g, n, b);
       pk[1] = sampled_pair<1>(w[1], g, n, b);
       pk[2] = sampled_pair<2>(w[2], g, n, b);
       pk[3] = sampled_pair<3>(w[3], g, n, b);
     } else {
-      const Philox4 x = rows_part != nullptr ? x4[i] : philox4x32_10(cg, row, step_lo, step_hi, d.seed_lo, d.seed_hi);
+      const Philox4 x = bits_of(row, i);
       pk[0] = sampled_pair_basis<BASIS, 0>(w[0], x, b);
       pk[1] = sampled_pair_basis<BASIS, 1>(w[1], x, b);
       pk[2] = sampled_pair_basis<BASIS, 2>(w[2], x, b);
       pk[3] = sampled_pair_basis<BASIS, 3>(w[3], x, b);
     }
   };
-  auto finish = [&](bool use_hw) {
-    if constexpr (FMT != 2) {
+  if constexpr (FMT != 2) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (!FULL && t.nv[i] == 0) continue;
-        const uint32_t row = row_base + r0 + 8 * i;
-        if constexpr (MX) {
-          const Noise n = rows_part != nullptr ? noise_planes(x4[i]) : group_noise(cg, d.row0 + row, step_lo, step_hi, d.seed_lo, d.seed_hi);
-          const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, use_hw);
-          store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
+    for (int i = 0; i < 4; ++i) {
+      if (!FULL && t.nv[i] == 0) continue;
+      const uint32_t row = row_base + r0 + 8 * i;
+      if constexpr (MX) {
+        const Noise n = noise_planes(bits_of(d.row0 + row, i));
+        const MxCodes c = sample_group_mx_fp8(t.v[i], n, b, USE_HW);
+        store_codes<FMT>(global_ptr<uint8_t>(d.p1) + (size_t)row * d.ldc, col, c, FULL ? 8 : t.nv[i]);
+      } else {
+        uint32_t pk[4];
+        sampled_group(t.v[i], d.row0 + row, i, pk);
+        i16x2 chain = {0, 0};
+        const u32x4 o = {cast_pair<FMT>(pk[0], b, USE_HW, chain), cast_pair<FMT>(pk[1], b, USE_HW, chain),
+                         cast_pair<FMT>(pk[2], b, USE_HW, chain), cast_pair<FMT>(pk[3], b, USE_HW, chain)};
+        GWS_GLOBAL uint16_t* dst = w_hat + (size_t)row * d.ld + col;
+        if (FULL || t.nv[i] == 8) {
+          if (STREAM) store16(dst, o);
+          else *(GWS_GLOBAL u32x4*)dst = o;
         } else {
-          uint32_t pk[4];
-          sampled_group(t.v[i], d.row0 + row, i, pk);
-          i16x2 chain = {0, 0};
-          const u32x4 o = {cast_pair<FMT>(pk[0], b, use_hw, chain), cast_pair<FMT>(pk[1], b, use_hw, chain),
-                           cast_pair<FMT>(pk[2], b, use_hw, chain), cast_pair<FMT>(pk[3], b, use_hw, chain)};
-          GWS_GLOBAL uint16_t* dst = w_hat + (size_t)row * d.ld + col;
-          if (FULL || t.nv[i] == 8) {
-            if (STREAM) store16(dst, o);
-            else *(GWS_GLOBAL u32x4*)dst = o;
-          } else {
-            store_partial(dst, o, t.nv[i]);
-          }
+          store_partial(dst, o, t.nv[i]);
         }
       }
     }
-  };
-  // FP6-E3M2: the 32-wide hardware converters (v_cvt_scalef32_pk32_bf6_bf16 and back) take
-  // a lane's whole tile at once, round to nearest even with gradual underflow and saturate
-  // at 28 * X (checked against the cast's definition on every finite BF16 input at several
-  // scales), so all four groups are sampled first and converted together.
-  auto finish_fp6 = [&]() {
+  } else {
+    // FP6-E3M2: the 32-wide hardware converters (v_cvt_scalef32_pk32_bf6_bf16 and back) take
+    // a lane's whole tile at once, round to nearest even with gradual underflow and saturate
+    // at 28 * X (checked against the cast's definition on every finite BF16 input at several
+    // scales), so all four groups are sampled first and converted together.
     typedef __bf16 bf16x32 __attribute__((ext_vector_type(32)));
     typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
     uint32_t pk[16];
@@ -254,10 +266,24 @@ __device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, con
         }
       }
     }
-  };
-  if constexpr (FMT == 2) finish_fp6();
-  else if (FMT == 1 && hw) finish(true);
-  else finish(false);
+  }
+}
+
+// Both phases for one tile; FP8-E4M3 takes the hardware converters only if neither block of this wavefront can
+// overflow (they give NaN where the cast saturates).
+template <int FMT, bool FULL, bool STREAM = true, bool MX = false, bool BT_PRE = false, int BASIS = kBasisBits>
+__device__ __forceinline__ void fwd_tile(uint32_t step_lo, uint32_t step_hi, const TileDesc& d, Tile& t,
+                                         uint32_t by, uint32_t col_base, uint32_t lane, float bt_pre = 0.0f,
+                                         const PhiloxRows* rows_part = nullptr) {
+  const BlockScale b = tile_scale<FMT, FULL, MX, BT_PRE, true>(d, t, by, col_base, lane, bt_pre);
+  if constexpr (FMT == 1) {
+    if (__builtin_amdgcn_ballot_w64(!b.hw_safe) == 0)
+      tile_apply<FMT, FULL, STREAM, MX, BASIS, true>(step_lo, step_hi, d, t, b, by, col_base, lane, rows_part, nullptr);
+    else
+      tile_apply<FMT, FULL, STREAM, MX, BASIS, false>(step_lo, step_hi, d, t, b, by, col_base, lane, rows_part, nullptr);
+  } else {
+    tile_apply<FMT, FULL, STREAM, MX, BASIS, false>(step_lo, step_hi, d, t, b, by, col_base, lane, rows_part, nullptr);
+  }
 }
 
 }  // namespace gws

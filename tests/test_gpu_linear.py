@@ -258,3 +258,63 @@ def test_config5_gemm_with_the_next_weight_sampled_alongside():
     rows_sel = tile_rows(8192, np.random.default_rng(6))
     run_next_case(8192, 2048, 5632, False, 2048, 5632, gws.FMT_FP8_E4M3, 6, rows_sel=rows_sel)   # too much to ride: two launches
     run_next_case(8192, 2048, 5632, False, 2048, 2048, gws.FMT_FP8_E4M3, 7, rows_sel=rows_sel)   # rides beside the last round of tiles
+
+
+def run_next_list(M, K, N, next_shapes, fmt, idx, step=5, rows_sel=None):
+    """gws_gemm_bf16_sample_next_n: Y against the fp64 GEMM, every listed weight against the oracle's forward pass."""
+    x = synth.make_activation(700 + idx, M, K).to(DEV)
+    w = synth.make_tensor(700 + idx, K, N, with_grad=False)["w"].to(DEV)
+    y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    descs, host = [], []
+    for k, (r, c) in enumerate(next_shapes):
+        ld = (c + 7) // 8 * 8
+        t = synth.make_tensor(720 + 10 * idx + k, r, c, ld=ld, with_grad=False)
+        nw = t["w"].to(DEV)
+        nbr, nbc = synth.n_blocks(r, c)
+        descs.append(gws.TensorDesc(rows=r, cols=c, ld=ld, seed=oracle.derive_seed(9, 10 * idx + k), w=nw, w_hat=nw.clone(),
+                                    bt=t["bt"].to(DEV), scale=torch.full((nbr, nbc), float("nan"), device=DEV)))
+        host.append(t)
+    gws.gws_gemm_bf16_sample_next_n(x, w, y, descs, fmt, step)
+    torch.cuda.synchronize()
+    check_y(synth.bits(y), synth.bits(x), synth.bits(w), False, rows_sel)
+    for d, t in zip(descs, host):
+        ref_q, ref_s = oracle.sample_fwd(synth.bits(t["w"]), t["bt"].numpy(), fmt, d.seed, step, cols=d.cols)
+        assert (synth.bits(d.w_hat) == ref_q).all(), ("w_hat", idx, d.rows, d.cols)
+        assert (d.scale.cpu().numpy().view(np.uint32) == ref_s.view(np.uint32)).all(), ("scale", idx, d.rows, d.cols)
+
+
+@pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
+def test_gemm_with_several_next_weights_sampled_alongside(fmt):
+    run_next_list(768, 192, 1280, [(128, 512), (64, 256), (96, 768)], fmt, 0)           # all three ride (whole 32 x 256 tiles)
+    run_next_list(768, 192, 1280, [(128, 512), (96, 300)], fmt, 1)                       # the ragged one: separate launch
+    run_next_list(768, 192, 1280, [(32, 256)] * 5 + [(64, 512)], fmt, 2)                 # more than ride at once: the rest after the GEMM
+    run_next_list(768, 192, 1280, [(96, 320), (128, 512)], fmt, 3)                       # first not of whole 32 x 256 tiles: rides alone
+    run_next_list(200, 96, 160, [(128, 512), (64, 256)], fmt, 4)                         # GEMM not on the large tile: all separate
+    run_next_list(768, 192, 1280, [(256, 512), (0, 256), (64, 256)], fmt, 5)             # an empty weight in the list
+    run_next_list(256, 64, 256, [(2048, 2048), (1024, 1024)], fmt, 6)                    # too much to ride beside one short tile
+
+
+def test_forced_riding_gives_the_same_bytes_for_both_riding_loops():
+    # include/gws_bench.h, gws_gemm_bf16_ride_probe: riders alone (no GEMM) and beside a GEMM, both riding loops
+    fmt, step = gws.FMT_FP8_E4M3, 8
+    t = synth.make_tensor(790, 512, 1280, with_grad=False)
+    seed = oracle.derive_seed(3, 790)
+    ref_q, ref_s = oracle.sample_fwd(synth.bits(t["w"]), t["bt"].numpy(), fmt, seed, step)
+    nw, nbt = t["w"].to(DEV), t["bt"].to(DEV)
+    x = synth.make_activation(791, 512, 128).to(DEV)
+    w = synth.make_tensor(791, 128, 768, with_grad=False)["w"].to(DEV)
+    for rider in (0, 1):
+        for with_gemm in (False, True):
+            for extra in (1, 7, 64):
+                d = gws.TensorDesc(rows=512, cols=1280, seed=seed, w=nw, w_hat=torch.zeros_like(nw), bt=nbt,
+                                   scale=torch.zeros(16, 40, device=DEV))
+                y = torch.zeros(512, 768, dtype=torch.bfloat16, device=DEV)
+                if with_gemm:
+                    gws.gws_gemm_bf16_ride_probe(x, w, y, d, fmt, step, extra, rider)
+                else:
+                    gws.gws_gemm_bf16_ride_probe(None, None, None, d, fmt, step, extra, rider)
+                torch.cuda.synchronize()
+                assert (synth.bits(d.w_hat) == ref_q).all(), (rider, with_gemm, extra)
+                assert (d.scale.cpu().numpy().view(np.uint32) == ref_s.view(np.uint32)).all()
+                if with_gemm:
+                    check_y(synth.bits(y), synth.bits(x), synth.bits(w), False)
