@@ -787,9 +787,8 @@ def linear_bench(torch, gws, synth, dev):
                                      "gws_gemm_bf16_sample_next (GEMM on w_hat of layer l, sampling of layer l+1 in the same launch)"},
             "gemm_sample_next": {"same_shape_next_ms": med["gemm_next"], "next_2048x2048_riding_ms": med["gemm_next_q"],
                                  "gemm_then_sample_2048x2048_ms": med["gemm_then_q"], "gemm_on_w_hat_alone_ms": t_plain_what,
-                                 "note": "a 2048 x 5632 next weight does not fit beside the last round of tiles (64 of 256 compute "
-                                         "units idle, one wavefront per SIMD) and is sampled by a second launch; a 2048 x 2048 one rides "
-                                         "in the GEMM's launch"},
+                                 "note": "the GEMM's 704 tiles leave 64 of 256 compute units idle in the last round; a 2048 x 5632 or a "
+                                         "2048 x 2048 next weight is sampled there, in the GEMM's launch"},
             "bwd_x": {"gemm_on_w_hat_ms": med["bwd_x"], "torch_matmul_ms": med["bwd_x_torch"],
                       "TFLOPs": 2.0 * M * K * N / med["bwd_x"] / 1e9},
             "bwd_w": {"gemm_with_dbt_epilogue_ms": med["bwd_w_fused"], "gemm_plain_ms": med["bwd_w_plain"],
