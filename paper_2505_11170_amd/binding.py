@@ -403,7 +403,7 @@ def gws_gemm_bf16_ride_probe(x, w, y, nxt: TensorDesc, fmt: int, step: int, extr
         ldx, ldw, ldy = int(x.stride(0)), int(w.stride(0)), int(y.stride(0))
     _check(L.gws_gemm_bf16_ride_probe(_p(x), M, K, ldx, _p(w), N, ldw, int(bool(w_is_nk)), _p(y), ldy, _marshal([nxt]),
                                       int(fmt), int(step), int(extra_workgroups), int(rider), _stream(stream)),
-           "gws_gemm_bf16_ride_probe", "gws_ride_plan")
+           "gws_gemm_bf16_ride_probe")
 
 
 def gws_copy_tiles(t: Sequence[TensorDesc], stream=None) -> None:

@@ -2,32 +2,38 @@
 // (internal to csrc/).
 //
 // Workgroup = 256 threads = 2x2 wavefronts, K-steps of 64; a wavefront owns 128 x 128 of the
-// output as 4x4 v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers per lane, one
-// wavefront per SIMD).
+// output as 8x8 v_mfma_f32_16x16x32_bf16 tiles (256 accumulator registers per lane, one
+// wavefront per SIMD).  The GEMM runs against the card's power limit, and on random operands
+// the 16x16x32 MFMA takes less energy per flop than the 32x32x16 one (a loop of MFMAs alone is
+// 15 % faster with it, with the LDS reads and loads of this kernel 11 %).
 //
 // Operand tiles travel global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
 // staging registers), into two stages per operand.  Such a load writes its 64 lanes to 1 KiB of
 // consecutive LDS, so the layout is unpadded and bank conflicts are avoided by choosing which
 // 16-byte chunk of the tile each lane fetches (an XOR swizzle of the chunk index):
 //   operand stored contraction-contiguous (X; a weight stored [N x K]): tile = 256 rows of
-//     128 bytes; chunk c of row r sits in slot c ^ (r % 8); one ds_read_b128 per MFMA operand;
+//     128 bytes; chunk c of row r sits in slot c ^ ((r / 2) % 8), so that any 16 rows a
+//     ds_read_b128 serves together (two rows share 64 banks) hit 16 different bank groups; one
+//     such read per MFMA operand;
 //   operand stored output-contiguous (a weight stored [K x N]; both operands of the
 //     weight-gradient GEMM): tile = 64 k-rows of 512 bytes; chunk c of row k sits in slot
 //     c ^ 4 (k % 4); read with the transposing LDS load (ds_read_b64_tr_b16: within 16 lanes,
 //     lanes 4j..4j+3 point at 16 consecutive outputs of row k0+j and lane i receives the four k
-//     of output o0+i), two per MFMA operand.
+//     of output o0+i; the four 16-lane groups take the four 8-deep parts of the MFMA's k = 32),
+//     two per MFMA operand.
 // The four stage arrays are separate LDS variables: that is how the compiler can tell that a
 // load into one stage does not feed the reads of the other, and does not wait for it.
 //
 // With one wavefront per SIMD nothing else hides latency, and left to itself the scheduler
 // puts each LDS read right before its use and the 16 loads of a K-step in one burst, both of
 // which stall the MFMA pipe.  The order of the main loop is therefore written out and pinned
-// (a scheduling barrier after every step): each MFMA is followed by at most one LDS read (for
-// the next 16-deep slice, into the other fragment buffer) and, in the last slice of a K-step,
-// one load.  The single barrier of a K-step sits before that last slice: by then every
-// wavefront has issued (and the barrier waits for) its reads of the stage, so the stage can be
-// refilled for the step after next, and the other stage, whose loads were issued a whole K-step
-// earlier, is complete and its first fragments can be fetched under the last 16 MFMAs.
+// (a scheduling barrier after every step): the 64 MFMAs of a 32-deep slice are interleaved
+// with the LDS reads of the next slice (into the other fragment buffer), at most one behind an
+// MFMA, and, in the second slice of a K-step, with its 16 loads, one behind every fourth MFMA.
+// The single barrier of a K-step sits between its two slices: by then every wavefront has
+// issued (and the barrier waits for) its reads of the stage, so the stage can be refilled for
+// the step after next, and the other stage, whose loads were issued a whole K-step earlier, is
+// complete and its first fragments can be fetched under the second slice's MFMAs.
 #pragma once
 
 #include "gws_device.h"
@@ -37,7 +43,8 @@ namespace gws {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define GWS_LDS __attribute__((address_space(3)))
 
@@ -101,9 +108,10 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   auto make_src = [&](bool oc, const uint16_t* p, uint32_t ld, uint32_t o0) {
     Src s;
     s.ld = ld;
-    if (!oc) {  // rows 64 wave + 8 q + lane/8; slot lane%8 holds chunk slot ^ (row % 8)
+    if (!oc) {  // rows 64 wave + 8 q + lane/8; slot lane%8 holds chunk slot ^ ((row / 2) % 8) = slot ^ (4 (q%2) + lane/16)
       s.base = (const GWS_GLOBAL char*)(p + (size_t)(o0 + 64 * wave) * ld);
-      s.voff[0] = s.voff[1] = ((lane >> 3) * ld + (((lane & 7) ^ (lane >> 3)) * 8)) * 2;
+      s.voff[0] = ((lane >> 3) * ld + (((lane & 7) ^ (0 + (lane >> 4))) * 8)) * 2;
+      s.voff[1] = ((lane >> 3) * ld + (((lane & 7) ^ (4 + (lane >> 4))) * 8)) * 2;
     } else {    // k-rows 16 wave + 2 q + lane/32; slot lane%32 holds chunk slot ^ 4 (k % 4), k % 4 = 2 (q%2) + lane/32
       const uint32_t kb = lane >> 5;
       s.base = (const GWS_GLOBAL char*)(p + (size_t)(16 * wave) * ld + o0);
@@ -125,53 +133,59 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   };
 
   // ---- fragment reads: per-lane element offsets into a stage ----
+  // A fragment of the 16x16x32 MFMA is 16 outputs x 32 k: lane l holds output l % 16, k = 8 (l / 16) .. + 7.
   const uint32_t li = lane & 15, grp = lane >> 4, sw = (li >> 2) & 3;
-  uint32_t a_off[4], b_off[4];   // contraction-contiguous: per ks; output-contiguous: per fragment index
+  uint32_t a_off[4], b_off[4];   // contraction-contiguous: [ks] (2 used); output-contiguous: [fragment / 2]
   auto make_off = [&](bool oc, uint32_t w, uint32_t (&off)[4]) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (!oc) off[t] = (128 * w + (lane & 31)) * 64 + (((2 * t + (lane >> 5)) ^ (lane & 7)) * 8);
-      else off[t] = ((grp >> 1) * 8 + (li >> 2)) * 256 + (16 * w + 4 * (t ^ sw) + 2 * (grp & 1) + ((li >> 1) & 1)) * 8 + (li & 1) * 4;
+      if (!oc) off[t] = (128 * w + li) * 64 + (((4 * (t & 1) + grp) ^ ((lane >> 1) & 7)) * 8);
+      else off[t] = (8 * grp + (li >> 2)) * 256 + (16 * w + 4 * (t ^ sw) + ((li >> 1) & 1)) * 8 + (li & 1) * 4;
     }
   };
   make_off(A_OC, wm, a_off);
   make_off(B_OC, wn, b_off);
-  // read `half` of fragment f (0..3) of slice ks from a stage
+  // read `half` of fragment f (0..7) of slice ks (0, 1) from a stage
   auto read_frag = [&](bool oc, const uint32_t (&off)[4], Frag8& fr, const uint16_t* stage, int ks, int f, int half) {
     if (!oc) {
-      fr.u = *(const u32x4*)(stage + off[ks] + f * 32 * 64);
+      fr.u = *(const u32x4*)(stage + off[ks] + f * 16 * 64);
     } else {
-      const uint16_t* p = stage + off[f] + ks * 16 * 256 + half * 4 * 256;
+      const uint16_t* p = stage + off[f >> 1] + (f & 1) * 16 + ks * 32 * 256 + half * 4 * 256;
       fr.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GWS_LDS i16x4*)p);
     }
   };
   constexpr int RA = A_OC ? 2 : 1, RB = B_OC ? 2 : 1;   // LDS reads per fragment
-  constexpr int NR = 4 * RA + 4 * RB;                   // reads per slice (<= 16)
-  Frag8 fa[2][4], fb[2][4];
+  constexpr int NR = 8 * RA + 8 * RB;                   // reads per slice: 16, 24 or 32
+  constexpr int RSTRIDE = 64 / NR;                      // one read every RSTRIDE MFMAs
+  Frag8 fa[2][8], fb[2][8];
   // read n (0..NR-1) of slice (stage, ks) into fragment buffer `buf`, in the order the MFMAs need them:
-  // A fragment 0, B fragments 0..3, A fragments 1..3
+  // A fragment 0, B fragments 0..7, A fragments 1..7
   auto read_n = [&](int buf, const uint16_t* As, const uint16_t* Bs, int ks, int n) {
     if (n < RA) {
       read_frag(A_OC, a_off, fa[buf][0], As, ks, 0, n);
-    } else if (n < RA + 4 * RB) {
+    } else if (n < RA + 8 * RB) {
       const int m = n - RA;
       read_frag(B_OC, b_off, fb[buf][m / RB], Bs, ks, m / RB, m % RB);
     } else {
-      const int m = n - RA - 4 * RB;
+      const int m = n - RA - 8 * RB;
       read_frag(A_OC, a_off, fa[buf][1 + m / RA], As, ks, 1 + m / RA, m % RA);
     }
   };
 
-  f32x16 acc[4][4];
+  // acc[i][j]: the MFMA takes the B fragment as its first operand, so that a lane ends up with four
+  // consecutive columns of one row: row 16 i + lane % 16, columns 16 j + 4 (lane / 16) .. + 3 of the wavefront tile
+  f32x4 acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
   auto mfma_n = [&](int buf, int n) {
-    const int i = n >> 2, j = n & 3;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i].v, fb[buf][j].v, acc[i][j], 0, 0, 0);
+    const int i = n >> 3, j = n & 7;
+    // written as assembly so that the accumulator is one register tuple, tied in and out: with the builtin the
+    // compiler moves accumulators between registers at every turn of the loop
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[buf][j].u), "v"(fa[buf][i].u));
   };
 
   // One K-step on the stage (Ac, Bc).  On entry fragment buffer 0 holds (or is receiving) slice 0
@@ -179,28 +193,27 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   // with the stages swapped, and K-step `kn` is on its way into (Ac, Bc).
   auto kstep = [&](uint16_t* Ac, uint16_t* Bc, uint16_t* An, uint16_t* Bn, uint32_t kn) {
 #pragma unroll
-    for (int ks = 0; ks < 3; ++ks) {
-#pragma unroll
-      for (int n = 0; n < 16; ++n) {
-        mfma_n(ks & 1, n);
+    for (int n = 0; n < 64; ++n) {
+      mfma_n(0, n);
+      __builtin_amdgcn_sched_barrier(0);
+      if (n % RSTRIDE == 0 && n / RSTRIDE < NR) {
+        read_n(1, Ac, Bc, 1, n / RSTRIDE);
         __builtin_amdgcn_sched_barrier(0);
-        if (n < NR) {
-          read_n((ks + 1) & 1, Ac, Bc, ks + 1, n);
-          __builtin_amdgcn_sched_barrier(0);
-        }
       }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of the other stage has landed
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
+    for (int n = 0; n < 64; ++n) {
       mfma_n(1, n);
       __builtin_amdgcn_sched_barrier(0);
-      load_n(Ac, Bc, kn, n);
-      __builtin_amdgcn_sched_barrier(0);
-      if (n < NR) {
-        read_n(0, An, Bn, 0, n);
+      if (n % 4 == 1) {
+        load_n(Ac, Bc, kn, n / 4);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (n % RSTRIDE == 0 && n / RSTRIDE < NR) {
+        read_n(0, An, Bn, 0, n / RSTRIDE);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -225,24 +238,29 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   if (kt < nk) kstep(A0, B0, A1, B1, last);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // the refetches have landed before the epilogue reuses LDS
   __syncthreads();
+  // the MFMAs are assembly to the compiler, which therefore does not count their latency: let the last
+  // one retire before anything reads an accumulator
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 7\n\ts_nop 7");
+  __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue: fp32 -> BF16 (RNE) into this wavefront's own stage array, 64 rows at a time,
-  // then 16-byte groups to global ----
-  // acc[i][j][e]: row 32 i + 8 (e/4) + 4 (lane/32) + e%4, column 32 j + lane%32 of the wavefront tile
+  // ---- epilogue: fp32 -> BF16 (RNE) into this wavefront's own stage array, 64 rows at a time
+  // (8 bytes per lane: its four consecutive columns), then 16-byte groups to global ----
   uint16_t* cs = wave == 0 ? A0 : wave == 1 ? A1 : wave == 2 ? B0 : B1;
   uint16_t* yw = y + (size_t)(m0 + 128 * wm) * ldy + n0 + 128 * wn;
   const uint32_t lr = lane >> 4, c = (lane & 15) * 8;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
 #pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2)
+    for (int i2 = 0; i2 < 4; ++i2)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const uint32_t row = 32 * i2 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-          cs[row * PC + 32 * j + (lane & 31)] = (uint16_t)bf16_rne_bits(acc[2 * h + i2][j][e]);
-        }
+      for (int j = 0; j < 8; ++j) {
+        const f32x4 v = acc[4 * h + i2][j];
+        u32x2 pk;
+        pk[0] = pack_bf16_rne(v[0], v[1]);
+        pk[1] = pack_bf16_rne(v[2], v[3]);
+        *(u32x2*)(cs + (16 * i2 + li) * PC + 16 * j + 4 * grp) = pk;
+      }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS writes have landed
     __builtin_amdgcn_wave_barrier();
 #pragma unroll 4
