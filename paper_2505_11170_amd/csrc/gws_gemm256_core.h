@@ -17,7 +17,8 @@
 //     such read per MFMA operand;
 //   operand stored output-contiguous (a weight stored [K x N]; both operands of the
 //     weight-gradient GEMM): tile = 64 k-rows of 512 bytes; chunk c of row k sits in slot
-//     c ^ 4 (k % 4); read with the transposing LDS load (ds_read_b64_tr_b16: within 16 lanes,
+//     c ^ 4 (k % 4) ^ 2 (k / 8 % 2) (the 32 lanes one such read serves together take four rows
+//     k % 4 of two row groups k / 8, and every row starts at bank 0); read with the transposing LDS load (ds_read_b64_tr_b16: within 16 lanes,
 //     lanes 4j..4j+3 point at 16 consecutive outputs of row k0+j and lane i receives the four k
 //     of output o0+i; the four 16-lane groups take the four 8-deep parts of the MFMA's k = 32),
 //     two per MFMA operand.
@@ -102,7 +103,7 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   // 1 KiB at (wave * 8 + q) * 1 KiB of the stage ----
   struct Src {
     const GWS_GLOBAL char* base;
-    uint32_t voff[2];   // per-lane byte offset (output-contiguous: depends on q % 2)
+    uint32_t voff[4];   // per-lane byte offset; which one an instruction q uses: vsel(oc, q)
     uint32_t ld;
   };
   auto make_src = [&](bool oc, const uint16_t* p, uint32_t ld, uint32_t o0) {
@@ -110,20 +111,22 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
     s.ld = ld;
     if (!oc) {  // rows 64 wave + 8 q + lane/8; slot lane%8 holds chunk slot ^ ((row / 2) % 8) = slot ^ (4 (q%2) + lane/16)
       s.base = (const GWS_GLOBAL char*)(p + (size_t)(o0 + 64 * wave) * ld);
-      s.voff[0] = ((lane >> 3) * ld + (((lane & 7) ^ (0 + (lane >> 4))) * 8)) * 2;
-      s.voff[1] = ((lane >> 3) * ld + (((lane & 7) ^ (4 + (lane >> 4))) * 8)) * 2;
-    } else {    // k-rows 16 wave + 2 q + lane/32; slot lane%32 holds chunk slot ^ 4 (k % 4), k % 4 = 2 (q%2) + lane/32
+      s.voff[0] = s.voff[2] = ((lane >> 3) * ld + (((lane & 7) ^ (0 + (lane >> 4))) * 8)) * 2;
+      s.voff[1] = s.voff[3] = ((lane >> 3) * ld + (((lane & 7) ^ (4 + (lane >> 4))) * 8)) * 2;
+    } else {    // k-rows k = 16 wave + 2 q + lane/32; slot lane%32 holds chunk slot ^ 4 (k % 4) ^ 2 (k/8 % 2),
+                // k % 4 = 2 (q%2) + lane/32, k/8 % 2 = q/4
       const uint32_t kb = lane >> 5;
       s.base = (const GWS_GLOBAL char*)(p + (size_t)(16 * wave) * ld + o0);
-      s.voff[0] = (kb * ld + (((lane & 31) ^ ((0 + kb) << 2)) * 8)) * 2;
-      s.voff[1] = (kb * ld + (((lane & 31) ^ ((2 + kb) << 2)) * 8)) * 2;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        s.voff[v] = (kb * ld + (((lane & 31) ^ ((2 * (v & 1) + kb) << 2) ^ ((v >> 1) << 1)) * 8)) * 2;
     }
     return s;
   };
   const Src sa = make_src(A_OC, a, lda, m0), sb = make_src(B_OC, b, ldb, n0);
   auto load1 = [&](bool oc, const Src& s, uint16_t* stage, uint32_t kt, int q) {
     const size_t uni = oc ? (size_t)(kt * TK + 2 * q) * s.ld : (size_t)(8 * q) * s.ld + kt * TK;   // elements
-    __builtin_amdgcn_global_load_lds((const GWS_GLOBAL void*)(s.base + uni * 2 + s.voff[q & 1]),
+    __builtin_amdgcn_global_load_lds((const GWS_GLOBAL void*)(s.base + uni * 2 + s.voff[oc ? (q & 1) + 2 * ((q >> 2) & 1) : (q & 1)]),
                                      (GWS_LDS void*)(stage + (wave * 8 + q) * 512), 16, 0, 0);
   };
   // load n (0..15) of a K-step: even n -> A, odd n -> B
@@ -140,7 +143,7 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       if (!oc) off[t] = (128 * w + li) * 64 + (((4 * (t & 1) + grp) ^ ((lane >> 1) & 7)) * 8);
-      else off[t] = (8 * grp + (li >> 2)) * 256 + (16 * w + 4 * (t ^ sw) + ((li >> 1) & 1)) * 8 + (li & 1) * 4;
+      else off[t] = (8 * grp + (li >> 2)) * 256 + (16 * w + 4 * (t ^ sw) + ((li >> 1) & 1)) * 8 + (li & 1) * 4 + (grp & 1) * 16;
     }
   };
   make_off(A_OC, wm, a_off);
@@ -150,7 +153,7 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
     if (!oc) {
       fr.u = *(const u32x4*)(stage + off[ks] + f * 16 * 64);
     } else {
-      const uint16_t* p = stage + off[f >> 1] + (f & 1) * 16 + ks * 32 * 256 + half * 4 * 256;
+      const uint16_t* p = stage + (off[f >> 1] ^ ((f & 1) * 16)) + ks * 32 * 256 + half * 4 * 256;
       fr.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GWS_LDS i16x4*)p);
     }
   };
@@ -182,7 +185,8 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
   auto mfma_n = [&](int buf, int n) {
-    const int i = n >> 3, j = n & 7;
+    // the B fragments go up and down again: at a change of the A fragment the other operand stays
+    const int i = n >> 3, j = (i & 1) ? 7 - (n & 7) : (n & 7);
     // written as assembly so that the accumulator is one register tuple, tied in and out: with the builtin the
     // compiler moves accumulators between registers at every turn of the loop
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[buf][j].u), "v"(fa[buf][i].u));
