@@ -226,14 +226,20 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   // Past the last K-step the loads refetch that step into the stage nobody reads any more and
   // the fragment reads go unused: no branches in the loop body.
   const uint32_t last = nk - 1;
+  // both stages are requested at once (one memory round trip in front of the first MFMA, not two)
 #pragma unroll
   for (int n = 0; n < 16; ++n) load_n(A0, B0, 0, n);
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  __syncthreads();
 #pragma unroll
   for (int n = 0; n < 16; ++n) load_n(A1, B1, last < 1 ? last : 1, n);
+  __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): the first stage has landed
+  __syncthreads();
 #pragma unroll
   for (int n = 0; n < NR; ++n) read_n(0, A0, B0, 0, n);
+  // the compiler does not know that the assembly statements are MFMAs: keep the zeroing of the accumulators
+  // (vector writes) the required wait states away from the first of them
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 3");
+  __builtin_amdgcn_sched_barrier(0);
   uint32_t kt = 0;
   for (; kt + 1 < nk; kt += 2) {
     kstep(A0, B0, A1, B1, kt + 2 < last ? kt + 2 : last);
