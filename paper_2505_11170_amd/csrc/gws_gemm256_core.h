@@ -8,9 +8,13 @@
 // 15 % faster with it, with the LDS reads and loads of this kernel 11 %).
 //
 // Operand tiles travel global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
-// staging registers), into two stages per operand.  Such a load writes its 64 lanes to 1 KiB of
-// consecutive LDS, so the layout is unpadded and bank conflicts are avoided by choosing which
-// 16-byte chunk of the tile each lane fetches (an XOR swizzle of the chunk index):
+// staging registers), the A operand into a ring of two stages, the B operand (the weight) into a
+// ring of three: 5 x 32 KiB, all of the 160 KiB of LDS.  In a training step the activations were
+// written just before and come from the caches, the weights come from HBM; the third B stage
+// doubles the time a weight load may take (about one K-step with two stages).  Such a load
+// writes its 64 lanes to 1 KiB of consecutive LDS, so the layout is unpadded and bank conflicts
+// are avoided by choosing which 16-byte chunk of the tile each lane fetches (an XOR swizzle of
+// the chunk index):
 //   operand stored contraction-contiguous (X; a weight stored [N x K]): tile = 256 rows of
 //     128 bytes; chunk c of row r sits in slot c ^ ((r / 2) % 8), so that any 16 rows a
 //     ds_read_b128 serves together (two rows share 64 banks) hit 16 different bank groups; one
@@ -18,12 +22,16 @@
 //   operand stored output-contiguous (a weight stored [K x N]; both operands of the
 //     weight-gradient GEMM): tile = 64 k-rows of 512 bytes; chunk c of row k sits in slot
 //     c ^ 4 (k % 4) ^ 2 (k / 8 % 2) (the 32 lanes one such read serves together take four rows
-//     k % 4 of two row groups k / 8, and every row starts at bank 0); read with the transposing LDS load (ds_read_b64_tr_b16: within 16 lanes,
+//     k % 4 of two row groups k / 8, and every row starts at bank 0); read with the transposing LDS load
+//     (ds_read_b64_tr_b16: within 16 lanes,
 //     lanes 4j..4j+3 point at 16 consecutive outputs of row k0+j and lane i receives the four k
 //     of output o0+i; the four 16-lane groups take the four 8-deep parts of the MFMA's k = 32),
 //     two per MFMA operand.
-// The four stage arrays are separate LDS variables: that is how the compiler can tell that a
-// load into one stage does not feed the reads of the other, and does not wait for it.
+// The stage arrays are separate LDS variables and the direct loads are issued from assembly
+// statements: the compiler orders every LDS read it cannot tell apart after every direct load
+// it knows of (s_waitcnt vmcnt(0)), which would expose the load latency in every K-step and
+// defeat the ring.  The waits for the loads are the explicit ones in front of the barriers
+// (loads complete in order: "all but the last 8" leaves the youngest B stage in flight).
 //
 // With one wavefront per SIMD nothing else hides latency, and left to itself the scheduler
 // puts each LDS read right before its use and the 16 loads of a K-step in one burst, both of
@@ -31,10 +39,10 @@
 // (a scheduling barrier after every step): the 64 MFMAs of a 32-deep slice are interleaved
 // with the LDS reads of the next slice (into the other fragment buffer), at most one behind an
 // MFMA, and, in the second slice of a K-step, with its 16 loads, one behind every fourth MFMA.
-// The single barrier of a K-step sits between its two slices: by then every wavefront has
-// issued (and the barrier waits for) its reads of the stage, so the stage can be refilled for
-// the step after next, and the other stage, whose loads were issued a whole K-step earlier, is
-// complete and its first fragments can be fetched under the second slice's MFMAs.
+// The single barrier of a K-step sits between its two slices: in front of it every wavefront
+// waits for its reads of the stages (so they can be refilled, A for the step after next, B for
+// the one after that) and for its share of the next step's stages, whose first fragments are
+// then fetched under the second slice's MFMAs.
 #pragma once
 
 #include "gws_device.h"
@@ -94,6 +102,7 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   __shared__ __attribute__((aligned(16))) uint16_t A1[STAGE];
   __shared__ __attribute__((aligned(16))) uint16_t B0[STAGE];
   __shared__ __attribute__((aligned(16))) uint16_t B1[STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t B2[STAGE];
 
   const uint32_t tid = threadIdx.x, lane = tid & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -126,8 +135,17 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   const Src sa = make_src(A_OC, a, lda, m0), sb = make_src(B_OC, b, ldb, n0);
   auto load1 = [&](bool oc, const Src& s, uint16_t* stage, uint32_t kt, int q) {
     const size_t uni = oc ? (size_t)(kt * TK + 2 * q) * s.ld : (size_t)(8 * q) * s.ld + kt * TK;   // elements
-    __builtin_amdgcn_global_load_lds((const GWS_GLOBAL void*)(s.base + uni * 2 + s.voff[oc ? (q & 1) + 2 * ((q >> 2) & 1) : (q & 1)]),
-                                     (GWS_LDS void*)(stage + (wave * 8 + q) * 512), 16, 0, 0);
+    // issued from an assembly statement: the compiler would order every later read of the stage arrays after all
+    // direct loads it knows of (vmcnt(0)), and the ring keeps loads in flight across the barrier on purpose; the
+    // waits for these loads are the explicit ones in front of the barriers
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(GWS_LDS void*)(stage + (wave * 8 + q) * 512);
+    // (m0, the LDS address register of such a load, is reserved to the compiler, which warns when told that it is
+    // overwritten; it has to be told)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(s.voff[oc ? (q & 1) + 2 * ((q >> 2) & 1) : (q & 1)]), "s"(s.base + uni * 2), "s"(lds_addr) : "m0", "memory");
+#pragma clang diagnostic pop
   };
   // load n (0..15) of a K-step: even n -> A, odd n -> B
   auto load_n = [&](uint16_t* As, uint16_t* Bs, uint32_t kt, int n) {
@@ -192,10 +210,12 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[buf][j].u), "v"(fa[buf][i].u));
   };
 
-  // One K-step on the stage (Ac, Bc).  On entry fragment buffer 0 holds (or is receiving) slice 0
-  // of this stage and the loads of the other stage (An, Bn) are in flight; on exit the same holds
-  // with the stages swapped, and K-step `kn` is on its way into (Ac, Bc).
-  auto kstep = [&](uint16_t* Ac, uint16_t* Bc, uint16_t* An, uint16_t* Bn, uint32_t kn) {
+  // One K-step on the stages (Ac, Bc).  The A operand lives in a ring of two stages, the B operand (the weight,
+  // which comes from HBM where the activations come from the caches) in a ring of three: K-step k computes on
+  // A[k % 2], B[k % 3]; its second slice requests A of K-step k + 2 (`ka`) into Ac and B of K-step k + 3 (`kb`) into Bc,
+  // the A loads first.  Loads complete in order, so "all but the last 8" at the barrier means: A and B of the next
+  // K-step have landed, the B loads of the K-step after it may still be in flight.
+  auto kstep = [&](uint16_t* Ac, uint16_t* Bc, uint16_t* An, uint16_t* Bn, uint32_t ka, uint32_t kb) {
 #pragma unroll
     for (int n = 0; n < 64; ++n) {
       mfma_n(0, n);
@@ -205,15 +225,16 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's share of the other stage has landed
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int n = 0; n < 64; ++n) {
       mfma_n(1, n);
       __builtin_amdgcn_sched_barrier(0);
       if (n % 4 == 1) {
-        load_n(Ac, Bc, kn, n / 4);
+        const int idx = n / 4;
+        if (idx < 8) load1(A_OC, sa, Ac, ka, idx);
+        else load1(B_OC, sb, Bc, kb, idx - 8);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (n % RSTRIDE == 0 && n / RSTRIDE < NR) {
@@ -223,16 +244,20 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
     }
   };
 
-  // Past the last K-step the loads refetch that step into the stage nobody reads any more and
+  // Past the last K-step the loads refetch that step into stages nobody reads any more and
   // the fragment reads go unused: no branches in the loop body.
   const uint32_t last = nk - 1;
-  // both stages are requested at once (one memory round trip in front of the first MFMA, not two)
+  auto cl = [&](uint32_t k) { return k < last ? k : last; };
+  // everything the rings hold is requested at once (one memory round trip in front of the first MFMA)
 #pragma unroll
   for (int n = 0; n < 16; ++n) load_n(A0, B0, 0, n);
 #pragma unroll
-  for (int n = 0; n < 16; ++n) load_n(A1, B1, last < 1 ? last : 1, n);
-  __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): the first stage has landed
-  __syncthreads();
+  for (int q = 0; q < 8; ++q) load1(A_OC, sa, A1, cl(1), q);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) load1(B_OC, sb, B1, cl(1), q);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) load1(B_OC, sb, B2, cl(2), q);
+  asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");   // the first stages have landed
 #pragma unroll
   for (int n = 0; n < NR; ++n) read_n(0, A0, B0, 0, n);
   // the compiler does not know that the assembly statements are MFMAs: keep the zeroing of the accumulators
@@ -241,13 +266,21 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   asm volatile("s_nop 3");
   __builtin_amdgcn_sched_barrier(0);
   uint32_t kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    kstep(A0, B0, A1, B1, kt + 2 < last ? kt + 2 : last);
-    kstep(A1, B1, A0, B0, kt + 3 < last ? kt + 3 : last);
+  for (; kt + 6 <= nk; kt += 6) {
+    kstep(A0, B0, A1, B1, cl(kt + 2), cl(kt + 3));
+    kstep(A1, B1, A0, B2, cl(kt + 3), cl(kt + 4));
+    kstep(A0, B2, A1, B0, cl(kt + 4), cl(kt + 5));
+    kstep(A1, B0, A0, B1, cl(kt + 5), cl(kt + 6));
+    kstep(A0, B1, A1, B2, cl(kt + 6), cl(kt + 7));
+    kstep(A1, B2, A0, B0, cl(kt + 7), cl(kt + 8));
   }
-  if (kt < nk) kstep(A0, B0, A1, B1, last);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // the refetches have landed before the epilogue reuses LDS
-  __syncthreads();
+  const uint32_t rem = nk - kt;
+  if (rem > 0) kstep(A0, B0, A1, B1, cl(kt + 2), cl(kt + 3));
+  if (rem > 1) kstep(A1, B1, A0, B2, cl(kt + 3), cl(kt + 4));
+  if (rem > 2) kstep(A0, B2, A1, B0, cl(kt + 4), cl(kt + 5));
+  if (rem > 3) kstep(A1, B0, A0, B1, cl(kt + 5), cl(kt + 6));
+  if (rem > 4) kstep(A0, B1, A1, B2, cl(kt + 6), cl(kt + 7));
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the refetches have landed before the epilogue reuses LDS
   // the MFMAs are assembly to the compiler, which therefore does not count their latency: let the last
   // one retire before anything reads an accumulator
   __builtin_amdgcn_sched_barrier(0);
