@@ -209,6 +209,22 @@ def test_large_tile_gemm_random_shapes_and_strides():
         assert (synth.bits(y_full)[:, N:] == 0).all(), (case, "padding of Y written")
 
 
+@pytest.mark.parametrize("w_is_nk", [False, True])
+def test_large_tile_gemm_every_number_of_k_steps(w_is_nk):
+    # the main loop is unrolled six K-steps with a tail of up to five, and the operand rings are primed for the
+    # first three: 1 .. 14 K-steps take every path through prologue, loop and tail; every element against fp64
+    M, N = 256, 512
+    for nk in range(1, 15):
+        K = 64 * nk
+        x = synth.make_activation(700 + nk, M, K).to(DEV)
+        wr, wc = (N, K) if w_is_nk else (K, N)
+        w = synth.make_tensor(700 + nk, wr, wc, with_grad=False)["w"].to(DEV)
+        y = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+        gws.gws_gemm_bf16(x, w, y, w_is_nk=w_is_nk)
+        torch.cuda.synchronize()
+        check_y(synth.bits(y), synth.bits(x), synth.bits(w), w_is_nk)
+
+
 def run_next_case(M, K, N, w_is_nk, next_rows, next_cols, fmt, idx, step=3, next_pad=0, rows_sel=None):
     """gws_gemm_bf16_sample_next: Y against the fp64 GEMM, the riding forward pass against the oracle."""
     x = synth.make_activation(500 + idx, M, K).to(DEV)

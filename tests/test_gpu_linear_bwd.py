@@ -61,6 +61,13 @@ def test_single_tile_and_several_tiles(w_is_nk):
     run_case(128, 768, 256, w_is_nk, 804, row0=256, col0=512)     # a shard: the origin enters the noise counter
 
 
+def test_every_number_of_k_steps():
+    # tokens are the contraction here: 1 .. 13 K-steps of 64 tokens take every path through the prologue, the
+    # six-fold unrolled loop and its tail
+    for nk in range(1, 14):
+        run_case(64 * nk, 256, 256, bool(nk & 1), 840 + 2 * nk)
+
+
 @pytest.mark.parametrize("w_is_nk", [False, True])
 def test_config5_shape(w_is_nk):
     M, K, N = 8192, 2048, 5632
