@@ -556,7 +556,7 @@ int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* 
 // descriptors, the number of extra workgroups and the riding loop to use.
 // Ride along when the 256-tile GEMM leaves compute units without a tile in its last round and the sampling fits
 // beside that round.  Measured on MI355X: a riding wavefront (one per SIMD, the GEMM's register allocation) takes
-// about 1.8 us per 32 x 64 tile in ride_tiles and 2.1 us in sample_tiles; a GEMM tile about 1.6 us per K-step of 64.
+// about 1.8 us per 32 x 64 tile in ride_tiles and 2.1 us in sample_tiles; a GEMM tile about 1.5 us per K-step of 64.
 static int plan_ride(const GemmArgs& g, bool gemm_empty, int64_t K, const gws_tensor* next, int n_next, int force_extra,
                      int rider, RideList& r, uint32_t& idle, int& use_rider) {
   memset(&r, 0, sizeof r);
@@ -569,7 +569,7 @@ static int plan_ride(const GemmArgs& g, bool gemm_empty, int64_t K, const gws_te
   idle = cus > 0 ? (uint32_t)((cus - tiles % cus) % cus) : 0u;
   if (force_extra >= 0) idle = (uint32_t)force_extra;
   if (idle == 0) return 0;
-  const double t_tile_us = (double)(K / 64) * 1.6 + 5.0;
+  const double t_tile_us = (double)(K / 64) * 1.5 + 5.0;
   int n_riding = 0;
   double t_sample_us = 0.0;
   uint32_t begin = 0;
