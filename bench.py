@@ -463,6 +463,34 @@ def _time_ms(torch, fn, iters, warmup=3):
     return e0.elapsed_time(e1) / iters
 
 
+def bwd_w_shapes_bench(torch, gws, synth, dev, tokens=8192):
+    """Weight gradient + dL/db_t of the four weight shapes of a 1B decoder layer: the one-kernel form, the form with
+    the tokens split into parts through a workspace (weights of few tiles), and torch.matmul(x.T, dy) (no dL/db_t)."""
+    out = {}
+    for name, K, N in (("qkv", 2048, 2560), ("o", 2048, 2048), ("gate_up", 2048, 5632), ("down", 5632, 2048)):
+        x = synth.make_activation(90, tokens, K, device=dev)
+        dy = (synth.make_activation(91, tokens, N, device=dev).float() * 1e-3).to(torch.bfloat16)
+        dw = torch.zeros(K, N, dtype=torch.bfloat16, device=dev)
+        d = gws.TensorDesc(rows=K, cols=N, seed=1, scale=torch.full((K // 32, N // 32), 1e-3, device=dev), dw=dw,
+                           dbt=torch.zeros(K // 32, N // 32, device=dev))
+        need = gws.gws_linear_bwd_w_workspace_bytes(d, tokens)
+        ws = torch.empty(need // 4, device=dev) if need else None
+        xt = x.t()
+        variants = {"one_kernel_ms": lambda: gws.gws_linear_bwd_w(x, dy, d, 3),
+                    "split_ms": lambda: gws.gws_linear_bwd_w_ws(x, dy, d, 3, ws),
+                    "torch_matmul_ms": lambda: torch.matmul(xt, dy, out=dw)}
+        bursts = {k: [] for k in variants}
+        for _ in range(5):
+            for k, fn in variants.items():
+                bursts[k].append(_time_ms(torch, fn, 6, warmup=1))
+        r = {k: sorted(v)[len(v) // 2] for k, v in bursts.items()}
+        r["tiles"] = (K // 256) * (N // 256)
+        r["workspace_MiB"] = need / 2 ** 20
+        r["parts"] = need // (r["tiles"] * 256 * 256 * 4) if need else 1
+        out[f"{name}_{K}x{N}"] = r
+    return out
+
+
 def mx_bench(torch, gws, synth, dev, shapes, params):
     """Forward pass writing MX element codes + E8M0 block scales instead of the BF16 container."""
     out = {}
@@ -796,6 +824,7 @@ def linear_bench(torch, gws, synth, dev):
                       "epilogue_overhead_pct": 100.0 * (med["bwd_w_fused"] - med["bwd_w_plain"]) / med["bwd_w_plain"],
                       "separate_kernel_overhead_pct": 100.0 * (med["bwd_w_unfused"] - med["bwd_w_plain"]) / med["bwd_w_plain"],
                       "TFLOPs_with_epilogue": 2.0 * M * K * N / med["bwd_w_fused"] / 1e9},
+            "bwd_w_layer_shapes": bwd_w_shapes_bench(torch, gws, synth, dev),
             "fused_in_operand_overhead_pct_vs_best_plain": 100.0 * (t_inop - best_plain) / best_plain,
             "unfused_overhead_pct_vs_own_plain": 100.0 * (t_unfused - t_plain) / t_plain,
             "unfused_overhead_pct_vs_best_plain": 100.0 * (min(t_unfused, t_unfused_torch) - best_plain) / best_plain,

@@ -232,6 +232,23 @@ int gws_linear_fwd_static(const void* x, int64_t M, int64_t K, int64_t ldx,
 int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy,
                      const gws_tensor* w, int w_is_nk, uint64_t step, void* stream);
 
+/* gws_linear_bwd_w for weights of few 256 x 256 tiles (a 2048 x 2048 weight has 64, on a part
+ * with 256 compute units): the M tokens are split into parts, each part's workgroups leave an
+ * fp32 partial tile in `workspace`, and a second kernel adds a tile's parts in a fixed order,
+ * rounds once to BF16 and writes dW and dL/db_t as above.  Same arguments, results within the
+ * same bounds (the fp32 additions are grouped by part; nothing depends on timing).
+ *   gws_linear_bwd_w_workspace_bytes(w, M): bytes the split would use for this weight and M
+ *     (host call; 0 when the one-kernel form is used: enough tiles, M too small, bad shape).
+ *   workspace : device memory, 16-byte aligned, workspace_bytes long, not overlapping x, dy or
+ *     dw (GWS_ERR_ALIGN / GWS_ERR_ALIAS); the library's only use of it is during this call's
+ *     kernels, its contents afterwards are unspecified.  With less than
+ *     gws_linear_bwd_w_workspace_bytes the tokens are split into as many parts as fit, with
+ *     room for fewer than two parts (or workspace NULL) this is gws_linear_bwd_w.            */
+size_t gws_linear_bwd_w_workspace_bytes(const gws_tensor* w, int64_t M);
+int gws_linear_bwd_w_ws(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy,
+                        const gws_tensor* w, int w_is_nk, uint64_t step,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Plain BF16 GEMM with the same tiling as gws_linear_fwd and no sampling:
  * Y = X * W (or X * W^T when w_is_nk).  The reference point the fused kernel's
  * overhead is measured against.  w is device BF16 with leading dimension ldw.     */

@@ -20,7 +20,7 @@ BASIS_BITS, BASIS_UNIFORM_BF16, BASIS_BOX_MULLER = 0, 1, 2
 
 # include/gws.h (the method) and include/gws_bench.h (measurement aids)
 EXPORTS = ("gws_sample_fwd", "gws_sample_bwd", "gws_sample_fwd_bi", "gws_sample_bwd_bi", "gws_sample_fwd_mx", "gws_linear_fwd", "gws_linear_fwd_mode",
-           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_gemm_bf16_sample_next_n", "gws_noise_packed",
+           "gws_linear_fwd_ws", "gws_linear_fwd_workspace_bytes", "gws_linear_fwd_static", "gws_linear_bwd_w", "gws_linear_bwd_w_ws", "gws_linear_bwd_w_workspace_bytes", "gws_gemm_bf16", "gws_gemm_bf16_sample_next", "gws_gemm_bf16_sample_next_n", "gws_noise_packed",
            "gws_sample_fwd_basis", "gws_sample_bwd_basis", "gws_noise_basis",
            "gws_derive_seed", "gws_status_string", "gws_version")
 BENCH_EXPORTS = ("gws_copy_tiles", "gws_block_absmax", "gws_sample_bwd_tuned", "gws_sample_fwd_tuned", "gws_gemm_bf16_ride_probe", "gws_ride_plan")
@@ -142,6 +142,10 @@ def load_library() -> ctypes.CDLL:
     L.gws_block_absmax.restype = ci
     L.gws_linear_bwd_w.argtypes = [vp, vp, i64, i64, i64, tp, ci, u64, vp]
     L.gws_linear_bwd_w.restype = ci
+    L.gws_linear_bwd_w_workspace_bytes.argtypes = [tp, i64]
+    L.gws_linear_bwd_w_workspace_bytes.restype = ctypes.c_size_t
+    L.gws_linear_bwd_w_ws.argtypes = [vp, vp, i64, i64, i64, tp, ci, u64, vp, ctypes.c_size_t, vp]
+    L.gws_linear_bwd_w_ws.restype = ci
     L.gws_gemm_bf16.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, vp]
     L.gws_gemm_bf16.restype = ci
     L.gws_sample_fwd_basis.argtypes = [tp, ci, ci, ci, u64, vp]
@@ -352,6 +356,20 @@ def gws_linear_bwd_w(x, dy, w: TensorDesc, step: int, w_is_nk: bool = False, str
     L = load_library()
     _check(L.gws_linear_bwd_w(_p(x), _p(dy), int(x.shape[0]), int(x.stride(0)), int(dy.stride(0)), _marshal([w]),
                               int(bool(w_is_nk)), int(step), _stream(stream)), "gws_linear_bwd_w")
+
+
+def gws_linear_bwd_w_workspace_bytes(w: TensorDesc, M: int) -> int:
+    """Bytes ``gws_linear_bwd_w_ws`` would use for this weight over ``M`` tokens (0: the one-kernel form)."""
+    L = load_library()
+    return int(L.gws_linear_bwd_w_workspace_bytes(_marshal([w]), int(M)))
+
+
+def gws_linear_bwd_w_ws(x, dy, w: TensorDesc, step: int, workspace, w_is_nk: bool = False, stream=None) -> None:
+    """``gws_linear_bwd_w`` with the tokens split into parts through ``workspace`` (a device tensor, or None)."""
+    L = load_library()
+    nbytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(L.gws_linear_bwd_w_ws(_p(x), _p(dy), int(x.shape[0]), int(x.stride(0)), int(dy.stride(0)), _marshal([w]),
+                                 int(bool(w_is_nk)), int(step), _p(workspace), nbytes, _stream(stream)), "gws_linear_bwd_w_ws")
 
 
 def gws_gemm_bf16(x, w, y, w_is_nk: bool = False, stream=None) -> None:

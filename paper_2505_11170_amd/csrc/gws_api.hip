@@ -505,8 +505,9 @@ int gws_linear_fwd(const void* x, int64_t M, int64_t K, int64_t ldx, const gws_t
   return gws_linear_fwd_mode(x, M, K, ldx, w, w_is_nk, fmt, step, y, ldy, GWS_LINEAR_AUTO, stream);
 }
 
-int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w,
-                     int w_is_nk, uint64_t step, void* stream) {
+// Arguments of the weight-gradient GEMM checked and put into the GEMM's terms.
+static int bwd_w_args(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w, int w_is_nk,
+                      uint64_t step, GemmArgs& g) {
   if (!w) return GWS_ERR_NULL;
   int rc = check_shape(*w);
   if (rc != GWS_OK) return rc;
@@ -519,7 +520,6 @@ int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int6
   if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(w->dw, 16) || !aligned(w->dbt, 4) || !aligned(w->scale, 4)) return GWS_ERR_ALIGN;
   const size_t dw_bytes = (size_t)w->rows * w->ld * 2;
   if (overlap2(w->dw, dw_bytes, x, (size_t)M * ldx * 2) || overlap2(w->dw, dw_bytes, dy, (size_t)M * ldy * 2)) return GWS_ERR_ALIAS;
-  GemmArgs g;
   memset(&g, 0, sizeof g);
   // C[rows x cols] = A^T B over the M tokens: A supplies the rows of the stored weight
   g.x = (const uint16_t*)(w_is_nk ? dy : x); g.ldx = (uint32_t)(w_is_nk ? ldy : ldx);
@@ -530,8 +530,51 @@ int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int6
   g.row0 = (uint32_t)w->row0; g.cg0 = (uint32_t)(w->col0 / 8);
   g.seed_lo = (uint32_t)w->seed; g.seed_hi = (uint32_t)(w->seed >> 32);
   g.step_lo = (uint32_t)step; g.step_hi = (uint32_t)(step >> 32);
-  if (!gemm256_tn_applicable(g)) return GWS_ERR_SHAPE;
+  return gemm256_tn_applicable(g) ? GWS_OK : GWS_ERR_SHAPE;
+}
+
+// Into how many parts the tokens are split so that a weight of few 256 x 256 tiles still fills the chip: as many
+// as keep all workgroups in one round, at least 8 K-steps of 64 tokens each, at most 8 (every part costs a pass
+// over an fp32 copy of the gradient in the second kernel).
+static uint32_t bwd_w_parts(int64_t rows, int64_t cols, int64_t M) {
+  const int64_t tiles = (rows / 256) * (cols / 256);
+  const int cus = compute_units();
+  if (tiles <= 0 || cus <= 0) return 1;
+  int64_t parts = cus / tiles;
+  if (parts > 8) parts = 8;
+  if (parts > M / 64 / 8) parts = M / 64 / 8;
+  return parts < 2 ? 1u : (uint32_t)parts;
+}
+
+int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w,
+                     int w_is_nk, uint64_t step, void* stream) {
+  GemmArgs g;
+  const int rc = bwd_w_args(x, dy, M, ldx, ldy, w, w_is_nk, step, g);
+  if (rc != GWS_OK) return rc;
   return launch_gemm256_tn(g, w->dbt != nullptr, (hipStream_t)stream);
+}
+
+size_t gws_linear_bwd_w_workspace_bytes(const gws_tensor* w, int64_t M) {
+  if (!w || w->rows <= 0 || w->cols <= 0 || (w->rows & 255) != 0 || (w->cols & 255) != 0 || M <= 0 || (M & 63) != 0) return 0;
+  const uint32_t parts = bwd_w_parts(w->rows, w->cols, M);
+  return parts < 2 ? 0 : (size_t)parts * (size_t)(w->rows / 256) * (size_t)(w->cols / 256) * 256 * 256 * sizeof(float);
+}
+
+int gws_linear_bwd_w_ws(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy, const gws_tensor* w,
+                        int w_is_nk, uint64_t step, void* workspace, size_t workspace_bytes, void* stream) {
+  GemmArgs g;
+  const int rc = bwd_w_args(x, dy, M, ldx, ldy, w, w_is_nk, step, g);
+  if (rc != GWS_OK) return rc;
+  uint32_t parts = bwd_w_parts(w->rows, w->cols, M);
+  const size_t per_part = gemm256_tn_split_bytes(g, 1);
+  if (workspace == nullptr) workspace_bytes = 0;
+  if (parts > workspace_bytes / per_part) parts = (uint32_t)(workspace_bytes / per_part);   // as many parts as the workspace holds
+  if (parts < 2) return launch_gemm256_tn(g, w->dbt != nullptr, (hipStream_t)stream);
+  if (!aligned(workspace, 16)) return GWS_ERR_ALIGN;
+  const size_t ws_bytes = gemm256_tn_split_bytes(g, parts);
+  if (overlap2(workspace, ws_bytes, w->dw, (size_t)w->rows * w->ld * 2) || overlap2(workspace, ws_bytes, x, (size_t)M * ldx * 2) ||
+      overlap2(workspace, ws_bytes, dy, (size_t)M * ldy * 2)) return GWS_ERR_ALIAS;
+  return launch_gemm256_tn_split(g, w->dbt != nullptr, (float*)workspace, parts, (hipStream_t)stream);
 }
 
 int gws_gemm_bf16(const void* x, int64_t M, int64_t K, int64_t ldx, const void* w, int64_t N, int64_t ldw,

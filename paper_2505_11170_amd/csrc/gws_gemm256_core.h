@@ -85,18 +85,52 @@ __device__ __forceinline__ void tile_of(uint32_t L, uint32_t mt, uint32_t nt, ui
   tile_m = band * 8 + r % mrows;
 }
 
-// C tile at (m0, n0) = sum over nk K-steps of A-tile * B-tile, written as BF16 (one RNE) to
-// y[(m0 + r) * ldy + n0 + c].
+// Half h (rows 64 h .. 64 h + 63) of a wavefront's 128 x 128 part of the result on its way out: fp32 -> BF16 (RNE)
+// into the wavefront's staging area `cs` (64 rows of pitch PC; 8 bytes per lane: its four consecutive columns),
+// then 16-byte groups to yw[(64 h + row) * ldy + col], each also handed to hook(it, row, col, v) with it = 16 h + the
+// 4-row step, row and col relative to the wavefront's part, lane = (row % 4, col / 8).
+// a4[i2][j][e]: row 64 h + 16 i2 + lane % 16, column 16 j + 4 (lane / 16) + e.
+template <class Hook>
+__device__ __forceinline__ void epilogue_bf16_half(const f32x4 (&a4)[4][8], int h, uint16_t* cs, uint16_t* yw, uint32_t ldy,
+                                                   uint32_t lane, Hook&& hook) {
+  using namespace g256;
+  const uint32_t li = lane & 15, grp = lane >> 4, lr = lane >> 4, c = (lane & 15) * 8;
+#pragma unroll
+  for (int i2 = 0; i2 < 4; ++i2)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const f32x4 v = a4[i2][j];
+      u32x2 pk;
+      pk[0] = pack_bf16_rne(v[0], v[1]);
+      pk[1] = pack_bf16_rne(v[2], v[3]);
+      *(u32x2*)(cs + (16 * i2 + li) * PC + 16 * j + 4 * grp) = pk;
+    }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS writes have landed
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+  for (int it = 0; it < 16; ++it) {
+    const uint32_t row = it * 4 + lr;
+    const u32x4 v = *(const u32x4*)(cs + row * PC + c);
+    *(u32x4*)(yw + (size_t)(64 * h + row) * ldy + c) = v;
+    hook(16 * h + it, 64 * h + row, c, v);
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // the reads are done before the staging area is written again
+  __builtin_amdgcn_wave_barrier();
+}
+
+// The accumulators of the C tile at (m0, n0) = sum over nk K-steps of A-tile * B-tile, handed to
+// finish(acc, cs, wave, lane) when the last MFMA has retired:
 //   A_OC = false: a[(m0 + r) * lda + k]   (contraction-contiguous)   true: a[k * lda + m0 + r]
 //   B_OC = false: b[(n0 + c) * ldb + k]                               true: b[k * ldb + n0 + c]
-// hook(it, row, col, v) is called for every 16-byte group of the BF16 result on its way out:
-// a wavefront writes its 128 x 128 part in 32 steps `it` of 4 rows, lane = (row % 4, col / 8).
+//   acc[i][j][e]: row 16 i + lane % 16, column 16 j + 4 (lane / 16) + e of the wavefront's 128 x 128 part, which
+//   starts at row 128 (wave / 2), column 128 (wave % 2) of the tile; cs: 64 x PC elements of LDS that are the
+//   wavefront's own from here on (a stage array nobody reads any more).
 // Requires nk >= 1 and all 256 threads; ends with every wavefront past its last LDS access
-// except its own epilogue staging (callers that loop over tiles put a barrier between tiles).
-template <bool A_OC, bool B_OC, class Hook>
-__device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uint32_t lda,
-                                             const uint16_t* __restrict__ b, uint32_t ldb, uint16_t* __restrict__ y,
-                                             uint32_t ldy, uint32_t nk, uint32_t m0, uint32_t n0, Hook&& hook) {
+// except its own staging area (callers that loop over tiles put a barrier between tiles).
+template <bool A_OC, bool B_OC, class Finish>
+__device__ __forceinline__ void gemm256_accumulate(const uint16_t* __restrict__ a, uint32_t lda,
+                                                   const uint16_t* __restrict__ b, uint32_t ldb, uint32_t nk, uint32_t m0,
+                                                   uint32_t n0, Finish&& finish) {
   using namespace g256;
   __shared__ __attribute__((aligned(16))) uint16_t A0[STAGE];
   __shared__ __attribute__((aligned(16))) uint16_t A1[STAGE];
@@ -290,39 +324,25 @@ __device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uin
   asm volatile("s_nop 7\n\ts_nop 7");
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue: fp32 -> BF16 (RNE) into this wavefront's own stage array, 64 rows at a time
-  // (8 bytes per lane: its four consecutive columns), then 16-byte groups to global ----
-  uint16_t* cs = wave == 0 ? A0 : wave == 1 ? A1 : wave == 2 ? B0 : B1;
-  uint16_t* yw = y + (size_t)(m0 + 128 * wm) * ldy + n0 + 128 * wn;
-  const uint32_t lr = lane >> 4, c = (lane & 15) * 8;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-#pragma unroll
-    for (int i2 = 0; i2 < 4; ++i2)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const f32x4 v = acc[4 * h + i2][j];
-        u32x2 pk;
-        pk[0] = pack_bf16_rne(v[0], v[1]);
-        pk[1] = pack_bf16_rne(v[2], v[3]);
-        *(u32x2*)(cs + (16 * i2 + li) * PC + 16 * j + 4 * grp) = pk;
-      }
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS writes have landed
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-      const uint32_t row = it * 4 + lr;
-      const u32x4 v = *(const u32x4*)(cs + row * PC + c);
-      *(u32x4*)(yw + (size_t)(64 * h + row) * ldy + c) = v;
-      hook(16 * h + it, 64 * h + row, c, v);
-    }
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // the reads are done before the second half overwrites them
-    __builtin_amdgcn_wave_barrier();
-  }
+  finish(acc, wave == 0 ? A0 : wave == 1 ? A1 : wave == 2 ? B0 : B1, wave, lane);
 }
 
 struct NoHook {
   __device__ __forceinline__ void operator()(int, uint32_t, uint32_t, const u32x4&) const {}
 };
+
+// The tile written as BF16 (one RNE) to y[(m0 + r) * ldy + n0 + c]; hook(it, row, col, v) is called for every
+// 16-byte group on its way out: a wavefront writes its 128 x 128 part in 32 steps `it` of 4 rows,
+// lane = (row % 4, col / 8).
+template <bool A_OC, bool B_OC, class Hook>
+__device__ __forceinline__ void gemm256_core(const uint16_t* __restrict__ a, uint32_t lda,
+                                             const uint16_t* __restrict__ b, uint32_t ldb, uint16_t* __restrict__ y,
+                                             uint32_t ldy, uint32_t nk, uint32_t m0, uint32_t n0, Hook&& hook) {
+  gemm256_accumulate<A_OC, B_OC>(a, lda, b, ldb, nk, m0, n0, [&](f32x4 (&acc)[8][8], uint16_t* cs, uint32_t wave, uint32_t lane) {
+    uint16_t* yw = y + (size_t)(m0 + 128 * (wave >> 1)) * ldy + n0 + 128 * (wave & 1);
+    epilogue_bf16_half(*reinterpret_cast<const f32x4 (*)[4][8]>(&acc[0]), 0, cs, yw, ldy, lane, hook);
+    epilogue_bf16_half(*reinterpret_cast<const f32x4 (*)[4][8]>(&acc[4]), 1, cs, yw, ldy, lane, hook);
+  });
+}
 
 }  // namespace gws

@@ -106,5 +106,9 @@ int compute_units();   // of the current device; 0 if the query fails
 // row-major (K = the contraction length); with_dbt adds Eq. 4's block reduction on y.
 bool gemm256_tn_applicable(const GemmArgs& g);
 int launch_gemm256_tn(const GemmArgs& g, bool with_dbt, hipStream_t stream);
+// the same result with the contraction of every tile split over `parts` (2 .. K / 64) workgroups: fp32 partial tiles in
+// `ws` (gemm256_tn_split_bytes, 16-byte aligned), added in a fixed order by a second kernel
+size_t gemm256_tn_split_bytes(const GemmArgs& g, uint32_t parts);
+int launch_gemm256_tn_split(const GemmArgs& g, bool with_dbt, float* ws, uint32_t parts, hipStream_t stream);
 
 }  // namespace gws

@@ -23,7 +23,9 @@ def f64(bits):
     return (np.ascontiguousarray(bits).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
-def run_case(M, K, N, w_is_nk, idx, step=4, rows_sel=None, pad=0, row0=0, col0=0):
+def run_case(M, K, N, w_is_nk, idx, step=4, rows_sel=None, pad=0, row0=0, col0=0, split=None):
+    """split: None = gws_linear_bwd_w; a number of bytes = gws_linear_bwd_w_ws with a workspace of that size
+    (-1: the size gws_linear_bwd_w_workspace_bytes names, which must then be positive)."""
     x = synth.make_activation(idx, M, K)
     dy = (synth.make_activation(idx + 1, M, N).float() * 1e-3).to(torch.bfloat16)   # upstream gradient ~ N(0, 1e-3)
     rows, cols = (N, K) if w_is_nk else (K, N)
@@ -36,7 +38,15 @@ def run_case(M, K, N, w_is_nk, idx, step=4, rows_sel=None, pad=0, row0=0, col0=0
     dbt = torch.full((nbr, nbc), float("nan"), device=DEV)
     d = gws.TensorDesc(rows=rows, cols=cols, seed=seed, scale=scale.to(DEV), dw=dw, dbt=dbt, ld=ld, row0=row0, col0=col0)
     xg, dyg = x.to(DEV), dy.to(DEV)
-    gws.gws_linear_bwd_w(xg, dyg, d, step, w_is_nk=w_is_nk)
+    if split is None:
+        gws.gws_linear_bwd_w(xg, dyg, d, step, w_is_nk=w_is_nk)
+    else:
+        want = gws.gws_linear_bwd_w_workspace_bytes(d, M)
+        if split < 0:
+            assert want > 0, ("no split planned", M, K, N)
+            split = want
+        ws = torch.full((max(split, 16) // 4,), float("nan"), device=DEV)          # stale contents must not matter
+        gws.gws_linear_bwd_w_ws(xg, dyg, d, step, ws[: split // 4], w_is_nk=w_is_nk)
     torch.cuda.synchronize()
     dw_bits = synth.bits(dw)
     assert (dw_bits[:, cols:] == 0).all()                       # padding columns are never written
@@ -93,6 +103,46 @@ def test_epilogue_agrees_with_the_separate_backward_kernel_and_plain_form():
     a, b = dbt3.cpu().numpy().astype(np.float64), dbt.astype(np.float64)
     _, _, asum = oracle.sample_bwd(np.ascontiguousarray(dw_bits), d.scale.cpu().numpy(), d.seed, 4)
     assert (np.abs(a - b) <= 1e-5 * np.abs(a) + 2e-6 * asum).all()
+
+
+@pytest.mark.parametrize("w_is_nk", [False, True])
+def test_tokens_split_into_parts(w_is_nk):
+    # few tiles: the contraction over the tokens is split (2 .. 8 parts, uneven where the K-steps do not divide),
+    # partial tiles go through the workspace and are added in a fixed order; dW and dL/db_t to the same bars
+    run_case(1024, 256, 256, w_is_nk, 860, split=-1)                  # 1 tile, 16 K-steps: 2 parts
+    run_case(2048, 512, 768, w_is_nk, 862, pad=8, split=-1)           # 6 tiles, 32 K-steps: 4 parts
+    run_case(4352, 768, 256, w_is_nk, 864, row0=256, col0=512, split=-1)   # 3 tiles, 68 K-steps: 8 parts of 8 or 9
+    # a workspace with room for three parts where eight were planned, and none at all
+    per_part = 3 * 256 * 256 * 4
+    run_case(4352, 768, 256, w_is_nk, 866, split=3 * per_part + 100)
+    run_case(1024, 256, 256, w_is_nk, 868, split=0)
+
+
+def test_config5_sized_weights_split_over_tokens():
+    # the 2048 x 2048 weight of the 1B layer over 8192 tokens: 64 tiles in 4 parts; a row in every 256-row tile
+    rng = np.random.default_rng(870)
+    sel = sorted({0, 2047} | {t * 256 + int(rng.integers(0, 256)) for t in range(8)})
+    run_case(8192, 2048, 2048, False, 870, rows_sel=sel, split=-1)
+    d = gws.TensorDesc(rows=2048, cols=5632, seed=1)
+    assert gws.gws_linear_bwd_w_workspace_bytes(d, 8192) == 0          # 176 tiles: the one-kernel form
+    assert gws.gws_linear_bwd_w_workspace_bytes(gws.TensorDesc(rows=2048, cols=2048, seed=1), 8192) == 4 * 64 * 256 * 256 * 4
+
+
+def test_workspace_argument_errors():
+    x = torch.zeros(1024, 256, dtype=torch.bfloat16, device=DEV)
+    dy = torch.zeros(1024, 256, dtype=torch.bfloat16, device=DEV)
+    dw = torch.zeros(256, 256, dtype=torch.bfloat16, device=DEV)
+    d = gws.TensorDesc(rows=256, cols=256, seed=1, dw=dw)
+    need = gws.gws_linear_bwd_w_workspace_bytes(d, 1024)
+    assert need == 2 * 256 * 256 * 4
+    ws = torch.zeros(need // 4 + 4, device=DEV)
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_bwd_w_ws(x, dy, d, 0, ws.view(torch.uint8)[4: 4 + need])      # not 16-byte aligned
+    assert e.value.status == 3
+    with pytest.raises(gws.GwsError) as e:
+        gws.gws_linear_bwd_w_ws(x, dy, gws.TensorDesc(rows=256, cols=256, seed=1, dw=ws.view(torch.bfloat16)[:65536].view(256, 256)), 0, ws)
+    assert e.value.status == 6                                                          # workspace on top of dW
+    torch.cuda.synchronize()
 
 
 def test_shape_and_argument_errors():
