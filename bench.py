@@ -659,8 +659,42 @@ def layer_bench(torch, gws, synth, dev, tokens=8192, layers=4):
     gws.gws_sample_fwd([ref], fmt, step[0])
     torch.cuda.synchronize()
     same = bool(torch.equal(ref.w_hat.view(torch.int16), W[1]["up"].w_hat.view(torch.int16)))
+    # ---- the layer's backward GEMMs: dX = dY * W^T (on w_hat in the sampled run) and dW = X^T dY (+ dL/db_t) ----
+    dys = {n: (synth.make_activation(62 + k, tokens, shapes[n][1], device=dev).float() * 1e-3).to(torch.bfloat16) for k, n in enumerate(order)}
+    dxs = {n: torch.empty(tokens, shapes[n][0], dtype=torch.bfloat16, device=dev) for n in order}
+    G = []                                    # per layer and weight: descriptors of the gradient, plain and with dL/db_t
+    ws_bytes = 0
+    for l in range(layers):
+        lg = {}
+        for n in order:
+            r, c = shapes[n]
+            dw = torch.empty(r, c, dtype=torch.bfloat16, device=dev)
+            lg[n] = (gws.TensorDesc(rows=r, cols=c, seed=W[l][n].seed, dw=dw),
+                     gws.TensorDesc(rows=r, cols=c, seed=W[l][n].seed, dw=dw, scale=W[l][n].scale, dbt=torch.empty(r // 32, c // 32, device=dev)))
+            ws_bytes = max(ws_bytes, gws.gws_linear_bwd_w_workspace_bytes(lg[n][0], tokens))
+        G.append(lg)
+    ws = torch.empty(ws_bytes // 4, device=dev) if ws_bytes else None
+
+    def bwd_plain():
+        for l in reversed(range(layers)):
+            for n in reversed(order):
+                gws.gws_gemm_bf16(dys[n], W[l][n].w, dxs[n], w_is_nk=True)          # the [K x N] weight read as [N' x K'] = dY * W^T
+                gws.gws_linear_bwd_w_ws(inp[n], dys[n], G[l][n][0], 0, ws)
+
+    def bwd_torch():
+        for l in reversed(range(layers)):
+            for n in reversed(order):
+                torch.matmul(dys[n], W[l][n].w.t(), out=dxs[n])
+                torch.matmul(inp[n].t(), dys[n], out=G[l][n][0].dw)
+
+    def bwd_sampled():
+        for l in reversed(range(layers)):
+            for n in reversed(order):
+                gws.gws_gemm_bf16(dys[n], W[l][n].w_hat, dxs[n], w_is_nk=True)
+                gws.gws_linear_bwd_w_ws(inp[n], dys[n], G[l][n][1], step[0], ws)      # dW and dL/db_t (Eq. 4) in one pass
+
     variants = {"plain": plain, "plain_torch": plain_torch, "plain_on_w_hat": plain_on_w_hat, "torch_on_w_hat": torch_on_w_hat,
-                "separate": separate, "riding": riding}
+                "separate": separate, "riding": riding, "bwd_plain": bwd_plain, "bwd_torch": bwd_torch, "bwd_sampled": bwd_sampled}
     for fn in variants.values():
         for _ in range(2):
             fn()
@@ -669,6 +703,7 @@ def layer_bench(torch, gws, synth, dev, tokens=8192, layers=4):
         for k, fn in variants.items():
             bursts[k].append(_time_ms(torch, fn, 3, warmup=1) / layers)
     med = {k: sorted(v)[len(v) // 2] for k, v in bursts.items()}
+    fb_plain, fb_torch, fb_sampled = med["plain"] + med["bwd_plain"], med["plain_torch"] + med["bwd_torch"], med["riding"] + med["bwd_sampled"]
     best_plain = min(med["plain"], med["plain_torch"])
     flop = 2.0 * tokens * sum(r * c for r, c in shapes.values())
     return {"tokens": tokens, "layers_in_a_row": layers, "gemms_per_layer": {n: [tokens, shapes[n][0], shapes[n][1]] for n in order},
@@ -679,6 +714,17 @@ def layer_bench(torch, gws, synth, dev, tokens=8192, layers=4):
             "riding_overhead_pct_vs_best_plain": 100.0 * (med["riding"] - best_plain) / best_plain,
             "riding_overhead_pct_vs_same_gemms_on_w_hat": 100.0 * (med["riding"] - med["plain_on_w_hat"]) / med["plain_on_w_hat"],
             "separate_overhead_pct_vs_same_gemms_on_w_hat": 100.0 * (med["separate"] - med["plain_on_w_hat"]) / med["plain_on_w_hat"],
+            "forward_and_backward": {
+                "ms_per_layer": {"plain_own": fb_plain, "plain_torch": fb_torch, "sampled": fb_sampled},
+                "sampled_overhead_pct_vs_own_plain": 100.0 * (fb_sampled - fb_plain) / fb_plain,
+                "sampled_overhead_pct_vs_best_plain": 100.0 * (fb_sampled - min(fb_plain, fb_torch)) / min(fb_plain, fb_torch),
+                "backward_overhead_pct_vs_own_plain": 100.0 * (med["bwd_sampled"] - med["bwd_plain"]) / med["bwd_plain"],
+                "note": "forward: the riding schedule; backward per weight: dX = dY * w_hat^T (gws_gemm_bf16) and dW = X^T dY with "
+                        "dL/db_t from the GEMM's epilogue (gws_linear_bwd_w_ws; the tokens split into parts for the weights of few "
+                        "tiles); plain: the same GEMMs on W without sampling and without dL/db_t; torch: torch.matmul for all 15 GEMMs",
+                "paper_context": "the paper's Table 1 reports 1.40 % (134M) to 5.30 % (3B) tokens/s overhead of a whole training "
+                                 "step on A100; this is the linear layers' GEMMs of one decoder layer alone, the part that overhead "
+                                 "is added to"},
             "carried_by_each_gemm": plan, "riding_matches_gws_sample_fwd": same,
             "sampled_params_per_layer": sum(r * c for r, c in shapes.values())}
 
