@@ -15,7 +15,7 @@ def _lib():
     ensure_built()
 
 
-def test_forward_backward_and_fused_linear_replay_from_a_graph():
+def test_forward_backward_and_linear_entry_points_replay_from_a_graph():
     fmt, step = gws.FMT_FP8_E4M3, 11
     shapes = [(768, 768), (96, 320), (40, 50)]
     descs, outs = [], []
@@ -45,8 +45,20 @@ def test_forward_backward_and_fused_linear_replay_from_a_graph():
     n_hat, n_scale = torch.zeros_like(tn["w"]), torch.zeros(24, 24, device=DEV)
     dnext = gws.TensorDesc(rows=768, cols=768, seed=6, w=tn["w"], w_hat=n_hat, bt=tn["bt"], scale=n_scale)
     outs += [y2, n_hat, n_scale]
+    # the weight gradient with dL/db_t, one kernel and with the tokens split through a workspace
+    dy = (synth.make_activation(713, 1024, N, device=DEV).float() * 1e-3).to(torch.bfloat16)
+    xb = synth.make_activation(714, 1024, K, device=DEV)
+    gscale = torch.full((K // 32, N // 32), 1e-3, device=DEV)
+    dgrad = [gws.TensorDesc(rows=K, cols=N, seed=7, scale=gscale, dw=torch.zeros(K, N, dtype=torch.bfloat16, device=DEV),
+                            dbt=torch.zeros(K // 32, N // 32, device=DEV)) for _ in range(2)]
+    gws_bytes = gws.gws_linear_bwd_w_workspace_bytes(dgrad[1], 1024)
+    assert gws_bytes > 0
+    gwork = torch.zeros(gws_bytes // 4, device=DEV)
+    outs += [dgrad[0].dw, dgrad[0].dbt, dgrad[1].dw, dgrad[1].dbt]
 
     def run():
+        gws.gws_linear_bwd_w(xb, dy, dgrad[0], step)
+        gws.gws_linear_bwd_w_ws(xb, dy, dgrad[1], step, gwork)
         gws.gws_sample_fwd(descs, fmt, step)
         gws.gws_sample_bwd(descs, step)
         gws.gws_linear_fwd(x, dlin, y, fmt, step)
