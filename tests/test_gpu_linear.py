@@ -167,6 +167,18 @@ def test_config5_fused_linear_8192x2048x5632_a_row_in_every_tile():
         run_case(M, K, N, False, gws.FMT_FP8_E4M3, bt=6.0, seed_id=5, rows_sel=rows_sel, mode=mode)
 
 
+def test_config5_input_gradient_8192x5632x2048_a_row_in_every_tile():
+    # dX = dY * W^T: the [K x N] weight of config 5 read as [N' x K'] = [2048 x 5632], 88 K-steps, one round of 256 tiles
+    M, K, N = 8192, 5632, 2048
+    dy = (synth.make_activation(51, M, K).float() * 1e-2).to(torch.bfloat16).to(DEV)
+    w = synth.make_tensor(52, N, K, bt=6.0, with_grad=False)["w"].to(DEV)
+    dx = torch.zeros(M, N, dtype=torch.bfloat16, device=DEV)
+    gws.gws_gemm_bf16(dy, w, dx, w_is_nk=True)
+    torch.cuda.synchronize()
+    rows_sel = tile_rows(M, np.random.default_rng(51))
+    check_y(synth.bits(dx), synth.bits(dy), synth.bits(w), True, rows_sel)
+
+
 def test_linear_mode_errors():
     x = synth.make_activation(4, 200, 96).to(DEV)
     t = synth.make_tensor(4, 96, 160, with_grad=False)
