@@ -171,8 +171,8 @@ int gws_sample_fwd_mx(const gws_tensor* t, const gws_mx_out* o, int n, int fmt, 
  *                           128 rows of X).  Any shape; w_hat/scale optional.
  *   GWS_LINEAR_TWO_KERNELS  the sampling kernel of gws_sample_fwd, then the plain GEMM on w_hat.
  *                           Needs w_hat/scale (GWS_ERR_NULL otherwise).
- *   GWS_LINEAR_AUTO         two kernels when w_hat/scale are given and M > 128, else in-operand:
- *                           the faster choice as measured on MI355X.
+ *   GWS_LINEAR_AUTO         two kernels when w_hat/scale are given (the faster choice at every M
+ *                           as measured on MI355X), else in-operand.
  * (Mode value 1 belonged to a retired kernel and is rejected with GWS_ERR_FORMAT.)
  * gws_linear_fwd is gws_linear_fwd_mode with GWS_LINEAR_AUTO.                              */
 #define GWS_LINEAR_AUTO 0

@@ -95,7 +95,7 @@ def run_case(M, K, N, w_is_nk, fmt, bt=None, seed_id=0, step=0, rows_sel=None, l
 @pytest.mark.parametrize("w_is_nk", [False, True])
 @pytest.mark.parametrize("fmt", [gws.FMT_BF16, gws.FMT_FP8_E4M3, gws.FMT_FP6_E3M2])
 def test_linear_small_shapes(w_is_nk, fmt):
-    run_case(128, 64, 128, w_is_nk, fmt, bt=6.0)                    # automatic choice: in-operand (M <= 128)
+    run_case(128, 64, 128, w_is_nk, fmt, bt=6.0)                    # automatic choice (w_hat given: sampling kernel + GEMM)
     run_case(200, 96, 160, w_is_nk, fmt, seed_id=1)                 # two kernels; ragged M, N not a tile multiple
     run_case(37, 32, 32, w_is_nk, fmt, seed_id=2, step=3)
     run_case(300, 256, 416, w_is_nk, fmt, seed_id=3, ldx_pad=8, ldy_pad=16)
