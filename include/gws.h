@@ -226,7 +226,8 @@ int gws_linear_fwd_static(const void* x, int64_t M, int64_t K, int64_t ldx,
  *        when w_is_nk != 0, [N x K].  Fields used: dw (out, required, [rows x ld]),
  *        dbt (out; NULL = plain GEMM), scale (in, required with dbt), rows, cols, ld,
  *        row0, col0, seed.
- * rows and cols must be multiples of 256 and M a multiple of 64 (GWS_ERR_SHAPE otherwise);
+ * rows and cols must be multiples of 256, M a multiple of 64 and ldx, ldy below 2^28
+ * (GWS_ERR_SHAPE otherwise);
  * M == 0 is an error, since dW would be undefined.  Given the same dW bytes,
  * gws_sample_bwd returns the same dL/db_t up to the order of the fp32 additions.        */
 int gws_linear_bwd_w(const void* x, const void* dy, int64_t M, int64_t ldx, int64_t ldy,

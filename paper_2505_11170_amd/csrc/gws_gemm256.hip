@@ -209,8 +209,10 @@ int compute_units() {
   return cus;
 }
 
+// The tile's direct loads address a lane as a scalar base plus a 32-bit byte offset of up to seven rows of the operand.
 bool gemm256_applicable(const GemmArgs& g) {
-  return g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 && g.M > 0 && g.N > 0 && g.K > 0;
+  return g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 && g.M > 0 && g.N > 0 && g.K > 0 &&
+         g.ldx < g256::kMaxLd && g.ldw < g256::kMaxLd;
 }
 
 int launch_gemm256(const GemmArgs& g, int w_is_nk, hipStream_t stream) {

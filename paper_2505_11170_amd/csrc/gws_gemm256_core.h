@@ -61,6 +61,7 @@ namespace g256 {
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int STAGE = 256 * 64;   // elements of one operand tile (32 KiB), either layout
 constexpr int PC = 128 + 8;       // epilogue pitch of a wavefront's staging rows (elements)
+constexpr uint32_t kMaxLd = 1u << 28;   // leading dimensions (elements) the 32-bit lane offsets of the loads reach: 7 rows x 2 bytes
 static_assert(64 * PC <= STAGE, "half a wavefront tile is staged in one stage array");
 }  // namespace g256
 

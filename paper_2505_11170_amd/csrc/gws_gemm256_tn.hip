@@ -135,7 +135,8 @@ __global__ __launch_bounds__(64) void gemm256_tn_sum_kernel(const GemmArgs g, co
 }
 
 bool gemm256_tn_applicable(const GemmArgs& g) {
-  return g.M > 0 && g.N > 0 && g.K > 0 && g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0;
+  return g.M > 0 && g.N > 0 && g.K > 0 && g.M % g256::TM == 0 && g.N % g256::TN == 0 && g.K % g256::TK == 0 &&
+         g.ldx < g256::kMaxLd && g.ldw < g256::kMaxLd;
 }
 
 int launch_gemm256_tn(const GemmArgs& g, bool with_dbt, hipStream_t stream) {
